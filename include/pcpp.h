@@ -1,0 +1,134 @@
+/*
+ * pcpp -- convolution on native points (PointCNN++) as MVMR, MI355X (gfx950) only.
+ *
+ * C ABI of libpcpp.so.  Plain pointers and sizes; every pointer is a DEVICE pointer unless the
+ * comment says HOST.  The caller owns every buffer (inputs, outputs, plan, workspace); the library
+ * allocates nothing on these paths and keeps no state between calls.
+ *
+ * Notation (paper -> here): output index i -> o, input index j -> i, kernel cell k;
+ * t = kernel resolution per axis, K = t^3; T = the triplet set {(o, i, k)}.
+ *
+ * Conventions shared by all calls
+ *   - return value: PCPP_OK or a negative PCPP_ERR_* code; pcpp_last_error() gives a message for
+ *     the calling thread.  Nothing is printed, nothing throws.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls are asynchronous on it, except
+ *     pcpp_build_triplets, which waits once for the triplet count.
+ *   - outputs are overwritten, never accumulated into; rows without a triplet are zero.
+ *   - indices are int32 (n_in, n_out, |T| < 2^31), segment offsets int64, coordinates fp32.
+ *   - feature tensors are row-major, 16-byte aligned; dtype codes below.
+ */
+#ifndef PCPP_H_
+#define PCPP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PCPP_OK                 0
+#define PCPP_ERR_INVALID_ARG   -1  /* null pointer, negative size, t < 1, bad radius, misaligned    */
+#define PCPP_ERR_CAPACITY      -2  /* triplet buffers too small; *n_triplets holds the needed count */
+#define PCPP_ERR_WORKSPACE     -3  /* workspace or plan buffer smaller than the matching *_bytes()  */
+#define PCPP_ERR_UNSUPPORTED   -4  /* dtype / shape outside what the library handles                */
+#define PCPP_ERR_HIP           -5  /* a HIP runtime call failed                                     */
+
+#define PCPP_F32   0   /* IEEE binary32                    */
+#define PCPP_BF16  1   /* bfloat16, round-to-nearest-even  */
+
+#define PCPP_PLAN_FWD        1   /* what pcpp_mvmr_fwd and pcpp_mvmr_bwd_weight read */
+#define PCPP_PLAN_BWD_INPUT  2   /* what pcpp_mvmr_bwd_input reads (only together with PCPP_PLAN_FWD) */
+
+#define PCPP_MAX_T  6            /* K = t^3 <= 216 */
+
+/* Message for the last error returned on the calling thread (never NULL). HOST. */
+const char *pcpp_last_error(void);
+
+/* Library version, major*100 + minor. */
+int pcpp_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Triplet construction: Sec. 3.2 "Definition" with the fixed radius search of Sec. 4.1, followed
+ * by the reordering of Sec. 3.3.2 (sort by kernel cell; here by (k, o, i)).
+ *
+ * (o, i, k) is in T iff |in_xyz[i] - out_xyz[o]|^2 <= r^2, the test being evaluated in binary64
+ * on the binary32 coordinates as (dx*dx + dy*dy) + dz*dz <= (double)r*(double)r without fused
+ * multiply-add.  k is the cell of d = in - out in the t x t x t grid tiling [-r, r]^3 around the
+ * output point: c_a = clamp(floor((d_a + r) * (t / (2r))), 0, t-1), k = (c_x*t + c_y)*t + c_z.
+ *
+ * Outputs
+ *   tri_o, tri_i, tri_k  [capacity] int32: T in ascending (k, o, i) order.  All three NULL =>
+ *                        count only (capacity, seg_offsets and plan are ignored).
+ *   seg_offsets          [K+1] int64: start of each cell's run; seg_offsets[K] = |T|.
+ *   n_triplets           HOST int64: |T|, also set when PCPP_ERR_CAPACITY is returned.
+ *   plan                 optional opaque buffer of pcpp_plan_bytes(...) bytes that the three
+ *                        compute calls need: per-(cell, output) neighbour counts and tile offsets
+ *                        for the forward / weight-gradient pass (PCPP_PLAN_FWD) and the same
+ *                        triplets regrouped by (k, i, o) for the input gradient
+ *                        (PCPP_PLAN_BWD_INPUT).  plan_flags selects the parts; NULL => none.
+ *   workspace            scratch of pcpp_build_triplets_workspace_bytes(...) bytes, 256-byte
+ *                        aligned; contents are undefined afterwards.
+ * in_xyz [n_in,3] and out_xyz [n_out,3] may alias (outputs at the inputs).
+ * Errors: INVALID_ARG (null xyz with n > 0, radius not finite or <= 0, t outside 1..PCPP_MAX_T,
+ * some but not all tri_* NULL), CAPACITY, WORKSPACE, UNSUPPORTED (|T| >= 2^31), HIP.
+ * Non-finite coordinates are not supported (undefined triplets, no fault).
+ * ------------------------------------------------------------------------------------------- */
+size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t);
+size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags);
+
+int pcpp_build_triplets(const float *in_xyz, int64_t n_in,
+                        const float *out_xyz, int64_t n_out,
+                        float radius, int t,
+                        int32_t *tri_o, int32_t *tri_i, int32_t *tri_k, int64_t capacity,
+                        int64_t *seg_offsets,
+                        int64_t *n_triplets,
+                        void *plan, size_t plan_bytes, int plan_flags,
+                        void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * MVMR forward, Eq. (1) of Sec. 3.1.1:  out[o, :] = sum_{(o,i,k) in T} W[k] x[i, :].
+ *   x   [n_in , c_in ]  in_dtype        w  [K, c_out, c_in] in_dtype (the paper's layout, Sec. 3.3.2)
+ *   out [n_out, c_out]  out_dtype (PCPP_F32, or PCPP_BF16 when in_dtype is PCPP_BF16)
+ * Products are accumulated in fp32.  tri_* / seg_offsets / plan must be exactly what one
+ * pcpp_build_triplets call produced for these n_in, n_out, K (with PCPP_PLAN_FWD); anything else
+ * is undefined behaviour.  workspace: pcpp_mvmr_workspace_bytes(...) bytes, 256-byte aligned.
+ * Errors: INVALID_ARG, WORKSPACE, UNSUPPORTED (c_in or c_out < 1 or > 1024, dtype combination).
+ * ------------------------------------------------------------------------------------------- */
+size_t pcpp_mvmr_workspace_bytes(int op /*0 fwd, 1 bwd_input, 2 bwd_weight*/, int64_t n_in, int64_t n_out,
+                                 int c_in, int c_out, int K, int in_dtype);
+
+int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out_dtype,
+                  int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                  const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                  const int64_t *seg_offsets, int64_t n_triplets,
+                  const void *plan, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * MVMR backward w.r.t. the input features, first gradient equation of Sec. 3.3.3:
+ *   dx[i, :] = sum_{(o,i,k) in T} W[k]^T dy[o, :].
+ *   dy [n_out, c_out] in_dtype,  w [K, c_out, c_in] in_dtype,  dx [n_in, c_in] out_dtype.
+ * Needs a plan built with PCPP_PLAN_BWD_INPUT.  Otherwise as pcpp_mvmr_fwd.
+ * ------------------------------------------------------------------------------------------- */
+int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, int out_dtype,
+                        int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                        const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                        const int64_t *seg_offsets, int64_t n_triplets,
+                        const void *plan, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Backward w.r.t. the weights (VVOR), Eq. (5) of Sec. 3.3.3:
+ *   dw[k] = sum_{(o,i,k) in T} dy[o, :] (outer) x[i, :],   dw [K, c_out, c_in] always fp32.
+ * Cells with no triplet get exact zeros.  Needs a plan built with PCPP_PLAN_FWD.
+ * ------------------------------------------------------------------------------------------- */
+int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype,
+                         int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                         const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                         const int64_t *seg_offsets, int64_t n_triplets,
+                         const void *plan, void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCPP_H_ */

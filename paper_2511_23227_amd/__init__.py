@@ -1,0 +1,11 @@
+"""pcpp: PointCNN++ convolution on native points as MVMR, hand-written HIP for MI355X (gfx950).
+
+The package is a thin ctypes binding over libpcpp.so (see include/pcpp.h).  Every step of the
+path -- hashed-grid radius search, reordering by (k, o), MVMR forward and both gradients -- runs
+in the library's kernels; PyTorch only provides device memory and the stream.
+"""
+from .binding import (PLAN_BWD_INPUT, PLAN_FWD, PcppError, Triplets, library, pcpp_build_triplets,
+                      pcpp_mvmr_bwd_input, pcpp_mvmr_bwd_weight, pcpp_mvmr_fwd)
+
+__all__ = ["PLAN_BWD_INPUT", "PLAN_FWD", "PcppError", "Triplets", "library", "pcpp_build_triplets",
+           "pcpp_mvmr_bwd_input", "pcpp_mvmr_bwd_weight", "pcpp_mvmr_fwd"]

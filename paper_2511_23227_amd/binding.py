@@ -1,0 +1,227 @@
+"""ctypes binding of libpcpp.so: argument marshalling only (torch tensors -> device pointers)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpcpp.so")
+
+PCPP_F32, PCPP_BF16 = 0, 1
+PLAN_FWD, PLAN_BWD_INPUT = 1, 2
+ERR_CAPACITY = -2
+
+EXPORTS = ("pcpp_last_error", "pcpp_version", "pcpp_build_triplets_workspace_bytes", "pcpp_plan_bytes",
+           "pcpp_build_triplets", "pcpp_mvmr_workspace_bytes", "pcpp_mvmr_fwd", "pcpp_mvmr_bwd_input",
+           "pcpp_mvmr_bwd_weight")
+
+
+class PcppError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"pcpp error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def library() -> ctypes.CDLL:
+    """Load libpcpp.so (building it first only if no built library exists).  Raises if unavailable."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build
+        build()
+    L = ctypes.CDLL(LIB_PATH)
+    i64, i32, f32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+    L.pcpp_last_error.restype = ctypes.c_char_p
+    L.pcpp_last_error.argtypes = []
+    L.pcpp_version.restype = i32
+    L.pcpp_build_triplets_workspace_bytes.restype = sz
+    L.pcpp_build_triplets_workspace_bytes.argtypes = [i64, i64, i32]
+    L.pcpp_plan_bytes.restype = sz
+    L.pcpp_plan_bytes.argtypes = [i64, i64, i32, i64, i32]
+    L.pcpp_build_triplets.restype = i32
+    L.pcpp_build_triplets.argtypes = [vp, i64, vp, i64, f32, i32, vp, vp, vp, i64, vp,
+                                      ctypes.POINTER(i64), vp, sz, i32, vp, sz, vp]
+    L.pcpp_mvmr_workspace_bytes.restype = sz
+    L.pcpp_mvmr_workspace_bytes.argtypes = [i32, i64, i64, i32, i32, i32, i32]
+    tail = [i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.pcpp_mvmr_fwd.restype = i32
+    L.pcpp_mvmr_fwd.argtypes = [vp, vp, vp, i32, i32] + tail
+    L.pcpp_mvmr_bwd_input.restype = i32
+    L.pcpp_mvmr_bwd_input.argtypes = [vp, vp, vp, i32, i32] + tail
+    L.pcpp_mvmr_bwd_weight.restype = i32
+    L.pcpp_mvmr_bwd_weight.argtypes = [vp, vp, vp, i32] + tail
+    if hasattr(L, "pcpp_debug_set_list_cap"):
+        L.pcpp_debug_set_list_cap.restype = i32
+        L.pcpp_debug_set_list_cap.argtypes = [i32]
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise PcppError(rc, library().pcpp_last_error().decode())
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return PCPP_F32
+    if t.dtype == torch.bfloat16:
+        return PCPP_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _bytes(n: int, device) -> torch.Tensor:
+    return torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class Triplets:
+    """Result of pcpp_build_triplets: T in (k, o, i) order plus the plan the compute calls read."""
+    tri_o: torch.Tensor
+    tri_i: torch.Tensor
+    tri_k: torch.Tensor
+    seg_offsets: torch.Tensor
+    n_triplets: int
+    n_in: int
+    n_out: int
+    t: int
+    plan: torch.Tensor
+    plan_flags: int
+
+    @property
+    def K(self) -> int:
+        return self.t ** 3
+
+
+def pcpp_count_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: float, t: int,
+                        workspace: torch.Tensor | None = None) -> int:
+    L = library()
+    n_in, n_out = in_xyz.shape[0], out_xyz.shape[0]
+    ws_bytes = L.pcpp_build_triplets_workspace_bytes(n_in, n_out, t)
+    ws = workspace if workspace is not None else _bytes(ws_bytes, in_xyz.device)
+    n = ctypes.c_int64(0)
+    _check(L.pcpp_build_triplets(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, float(radius), int(t), None, None, None,
+                                 0, None, ctypes.byref(n), None, 0, 0, _ptr(ws), ws.numel(), _stream()))
+    return int(n.value)
+
+
+def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: float, t: int,
+                        plan_flags: int = PLAN_FWD | PLAN_BWD_INPUT, capacity: int | None = None,
+                        buffers: dict | None = None) -> Triplets:
+    """Triplet construction (Sec. 3.2 with the fixed-radius search of Sec. 4.1) and reordering by (k, o, i).
+
+    in_xyz [n_in,3], out_xyz [n_out,3]: contiguous float32 CUDA tensors.  Without `capacity` the count is
+    taken first by a count-only call and the buffers are sized exactly.  `buffers` may carry preallocated
+    'tri_o','tri_i','tri_k','seg_offsets','plan','workspace' tensors to reuse.
+    """
+    L = library()
+    assert in_xyz.is_cuda and out_xyz.is_cuda and in_xyz.dtype == torch.float32 and out_xyz.dtype == torch.float32
+    assert in_xyz.is_contiguous() and out_xyz.is_contiguous()
+    dev = in_xyz.device
+    n_in, n_out = int(in_xyz.shape[0]), int(out_xyz.shape[0])
+    K = t ** 3
+    buffers = buffers or {}
+    ws_bytes = L.pcpp_build_triplets_workspace_bytes(n_in, n_out, t)
+    if ws_bytes == 0:
+        raise PcppError(-1, "invalid sizes or t")
+    ws = buffers.get("workspace")
+    if ws is None or ws.numel() < ws_bytes:
+        ws = _bytes(ws_bytes, dev)
+    if capacity is None:
+        capacity = pcpp_count_triplets(in_xyz, out_xyz, radius, t, ws)
+    cap = max(int(capacity), 1)
+
+    def buf(name, numel, dtype):
+        b = buffers.get(name)
+        if b is None or b.numel() < numel or b.dtype != dtype:
+            b = torch.empty(numel, dtype=dtype, device=dev)
+        return b
+
+    tri_o, tri_i, tri_k = (buf(nm, cap, torch.int32) for nm in ("tri_o", "tri_i", "tri_k"))
+    seg = buf("seg_offsets", K + 1, torch.int64)
+    plan_bytes = L.pcpp_plan_bytes(n_in, n_out, t, cap, plan_flags) if plan_flags else 0
+    plan = buffers.get("plan")
+    if plan_flags and (plan is None or plan.numel() < plan_bytes):
+        plan = _bytes(plan_bytes, dev)
+    n = ctypes.c_int64(0)
+    rc = L.pcpp_build_triplets(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, float(radius), int(t),
+                               _ptr(tri_o), _ptr(tri_i), _ptr(tri_k), cap, _ptr(seg), ctypes.byref(n),
+                               _ptr(plan) if plan_flags else None, plan.numel() if plan_flags else 0, plan_flags,
+                               _ptr(ws), ws.numel(), _stream())
+    if rc == ERR_CAPACITY:
+        raise PcppError(rc, f"capacity {cap} too small, need {n.value}")
+    _check(rc)
+    nt = int(n.value)
+    return Triplets(tri_o[:nt], tri_i[:nt], tri_k[:nt], seg[:K + 1], nt, n_in, n_out, t, plan, plan_flags)
+
+
+def _mvmr_ws(op, T: Triplets, c_in, c_out, code, dev, workspace):
+    need = library().pcpp_mvmr_workspace_bytes(op, T.n_in, T.n_out, c_in, c_out, T.K, code)
+    if workspace is None or workspace.numel() < need:
+        workspace = _bytes(need, dev)
+    return workspace
+
+
+def pcpp_mvmr_fwd(x: torch.Tensor, w: torch.Tensor, T: Triplets, out: torch.Tensor | None = None,
+                  out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Eq. (1): out[o] = sum_{(o,i,k) in T} W[k] x[i];  x [n_in,c_in], w [K,c_out,c_in] -> out [n_out,c_out]."""
+    L = library()
+    assert x.is_cuda and x.is_contiguous() and w.is_contiguous() and x.dtype == w.dtype
+    K, c_out, c_in = w.shape
+    assert K == T.K and x.shape == (T.n_in, c_in)
+    if out is None:
+        out = torch.empty((T.n_out, c_out), dtype=out_dtype, device=x.device)
+    ws = _mvmr_ws(0, T, c_in, c_out, _dtype_code(x), x.device, workspace)
+    _check(L.pcpp_mvmr_fwd(_ptr(x), _ptr(w), _ptr(out), _dtype_code(x), _dtype_code(out), T.n_in, T.n_out, c_in, c_out,
+                           K, _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets), T.n_triplets,
+                           _ptr(T.plan), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def pcpp_mvmr_bwd_input(dy: torch.Tensor, w: torch.Tensor, T: Triplets, dx: torch.Tensor | None = None,
+                        out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Sec. 3.3.3: dx[i] = sum_{(o,i,k) in T} W[k]^T dy[o];  dy [n_out,c_out] -> dx [n_in,c_in]."""
+    L = library()
+    assert dy.is_cuda and dy.is_contiguous() and w.is_contiguous() and dy.dtype == w.dtype
+    K, c_out, c_in = w.shape
+    assert K == T.K and dy.shape == (T.n_out, c_out)
+    if not (T.plan_flags & PLAN_BWD_INPUT):
+        raise PcppError(-1, "triplets were built without PLAN_BWD_INPUT")
+    if dx is None:
+        dx = torch.empty((T.n_in, c_in), dtype=out_dtype, device=dy.device)
+    ws = _mvmr_ws(1, T, c_in, c_out, _dtype_code(dy), dy.device, workspace)
+    _check(L.pcpp_mvmr_bwd_input(_ptr(dy), _ptr(w), _ptr(dx), _dtype_code(dy), _dtype_code(dx), T.n_in, T.n_out, c_in,
+                                 c_out, K, _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets),
+                                 T.n_triplets, _ptr(T.plan), _ptr(ws), ws.numel(), _stream()))
+    return dx
+
+
+def pcpp_mvmr_bwd_weight(x: torch.Tensor, dy: torch.Tensor, T: Triplets, dw: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Eq. (5): dW[k] = sum_{(o,i,k) in T} dy[o] (outer) x[i] -> float32 [K,c_out,c_in]."""
+    L = library()
+    assert x.is_cuda and x.is_contiguous() and dy.is_contiguous() and x.dtype == dy.dtype
+    c_in, c_out = x.shape[1], dy.shape[1]
+    assert x.shape[0] == T.n_in and dy.shape[0] == T.n_out
+    if dw is None:
+        dw = torch.empty((T.K, c_out, c_in), dtype=torch.float32, device=x.device)
+    ws = _mvmr_ws(2, T, c_in, c_out, _dtype_code(x), x.device, workspace)
+    _check(L.pcpp_mvmr_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), _dtype_code(x), T.n_in, T.n_out, c_in, c_out, T.K,
+                                  _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets), T.n_triplets,
+                                  _ptr(T.plan), _ptr(ws), ws.numel(), _stream()))
+    return dw

@@ -1,0 +1,612 @@
+// Triplet construction on the GPU: hashed uniform grid, fixed-radius query with local
+// voxelisation (Sec. 3.2 "Definition"; fixed radius search of Sec. 4.1), and the reordering of
+// Sec. 3.3.2 done as a counting sort on the composite key (k, centre): the query's count pass is
+// the histogram, a prefix sum gives every (k, centre) run its place, the fill pass writes each
+// triplet straight to its final position with ties ordered by the other index.
+//
+// This file is compiled with -ffp-contract=off: the inclusion test and the cell index are a fixed
+// sequence of binary64 operations (see pcpp.h) and must not be fused.
+#include <math.h>
+
+#include "pcpp_internal.h"
+
+namespace pcpp {
+
+namespace {
+
+constexpr unsigned long long EMPTY_KEY = ~0ull;
+constexpr int CELL_BIAS = 1 << 20;
+constexpr double CELL_CLAMP = (double)((1 << 20) - 2);   // +-1 stencil steps stay inside 21 bits
+constexpr int SEARCH_THREADS = 256;
+constexpr int SEARCH_WAVES = SEARCH_THREADS / 64;
+constexpr int LIST_CAP_MAX = 1024;                        // neighbours of one centre kept in LDS
+
+__device__ inline uint32_t hash_key(unsigned long long k)
+{
+    k ^= k >> 33; k *= 0xff51afd7ed558ccdULL;
+    k ^= k >> 33; k *= 0xc4ceb9fe1a85ec53ULL;
+    k ^= k >> 33;
+    return (uint32_t)k;
+}
+
+__device__ inline int grid_coord(float p, double inv_g)
+{
+    double u = floor((double)p * inv_g);
+    u = fmin(fmax(u, -CELL_CLAMP), CELL_CLAMP);      // NaN falls to a bound; no out-of-range key
+    return (int)u;
+}
+
+__device__ inline unsigned long long pack_key(int cx, int cy, int cz)
+{
+    return ((unsigned long long)(uint32_t)(cx + CELL_BIAS) << 42) |
+           ((unsigned long long)(uint32_t)(cy + CELL_BIAS) << 21) |
+           (unsigned long long)(uint32_t)(cz + CELL_BIAS);
+}
+
+// ---- hashed grid over the candidate set ------------------------------------------------------
+
+__global__ __launch_bounds__(256) void grid_insert(const float *__restrict__ xyz, int64_t n, double inv_g,
+                                                   unsigned long long *__restrict__ keys,
+                                                   uint32_t *__restrict__ slot_cnt, uint32_t mask,
+                                                   uint32_t *__restrict__ point_slot)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const unsigned long long key = pack_key(grid_coord(xyz[3 * p], inv_g), grid_coord(xyz[3 * p + 1], inv_g),
+                                            grid_coord(xyz[3 * p + 2], inv_g));
+    uint32_t slot = hash_key(key) & mask;
+    // the table has at least twice as many slots as points, so an empty slot is always reached
+    for (;;) {
+        unsigned long long prev = atomicCAS(&keys[slot], EMPTY_KEY, key);
+        if (prev == EMPTY_KEY || prev == key) break;
+        slot = (slot + 1) & mask;
+    }
+    atomicAdd(&slot_cnt[slot], 1u);
+    point_slot[p] = slot;
+}
+
+__global__ __launch_bounds__(256) void grid_scatter(const float *__restrict__ xyz, int64_t n,
+                                                    const uint32_t *__restrict__ point_slot,
+                                                    const uint32_t *__restrict__ slot_start,
+                                                    uint32_t *__restrict__ cursor, float4 *__restrict__ pts)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const uint32_t slot = point_slot[p];
+    const uint32_t pos = slot_start[slot] + atomicAdd(&cursor[slot], 1u);
+    pts[pos] = make_float4(xyz[3 * p], xyz[3 * p + 1], xyz[3 * p + 2], __int_as_float((int)p));
+}
+
+struct GridView {
+    const unsigned long long *keys;
+    const uint32_t *slot_start;   // [slots + 1]
+    const float4 *pts;            // candidates grouped by grid cell; .w carries the original index
+    uint32_t mask;
+    double inv_g;
+};
+
+struct QueryParams {
+    double R;         // (double)radius
+    double r2;        // R * R
+    double inv_cell;  // t / (2 R)
+    int t;
+};
+
+__device__ inline uint32_t wave_incl_scan_u32(uint32_t v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t u = __shfl_up(v, d, 64);
+        if (lane >= d) v += u;
+    }
+    return v;
+}
+
+// Candidates of one centre, held across the lanes of a wave: lane j < 27 owns stencil cell j.
+// Every method must be called by all 64 lanes of the wave (it uses cross-lane reads).
+template <bool SWAP>
+struct Candidates {
+    double cx, cy, cz;       // centre coordinate
+    uint32_t my_start;       // lane j: first candidate of stencil cell j
+    uint32_t my_excl;        // lane j: candidates in cells before j
+    uint32_t total;
+
+    __device__ inline void open(const float *__restrict__ centres, int64_t a, const GridView &g, int lane)
+    {
+        const float fx = centres[3 * a], fy = centres[3 * a + 1], fz = centres[3 * a + 2];
+        cx = (double)fx; cy = (double)fy; cz = (double)fz;
+        uint32_t cnt = 0;
+        my_start = 0;
+        if (lane < 27) {
+            const int gx = grid_coord(fx, g.inv_g) + lane / 9 - 1;
+            const int gy = grid_coord(fy, g.inv_g) + (lane / 3) % 3 - 1;
+            const int gz = grid_coord(fz, g.inv_g) + lane % 3 - 1;
+            const unsigned long long key = pack_key(gx, gy, gz);
+            uint32_t slot = hash_key(key) & g.mask;
+            for (;;) {
+                const unsigned long long kk = g.keys[slot];
+                if (kk == key) {
+                    my_start = g.slot_start[slot];
+                    cnt = g.slot_start[slot + 1] - my_start;
+                    break;
+                }
+                if (kk == EMPTY_KEY) break;
+                slot = (slot + 1) & g.mask;
+            }
+        }
+        const uint32_t incl = wave_incl_scan_u32(cnt, lane);
+        my_excl = incl - cnt;
+        total = __shfl(incl, 63, 64);
+    }
+
+    // Candidate number idx (idx may differ per lane).  Returns whether it is a neighbour;
+    // b = its original index, k = its kernel cell.
+    __device__ inline bool fetch(uint32_t idx, const GridView &g, const QueryParams &q, int &b, int &k) const
+    {
+        const bool in_range = idx < total;
+        const uint32_t id = in_range ? idx : 0u;
+        int j = 0;
+#pragma unroll
+        for (int step = 16; step >= 1; step >>= 1) {
+            const int c = j + step;
+            const int cc = c <= 26 ? c : 26;
+            const uint32_t e = __shfl(my_excl, cc, 64);
+            if (c <= 26 && e <= id) j = c;
+        }
+        const uint32_t s = __shfl(my_start, j, 64);
+        const uint32_t e = __shfl(my_excl, j, 64);
+        bool hit = false;
+        b = 0; k = 0;
+        if (in_range) {
+            const float4 p = g.pts[s + (id - e)];
+            b = __float_as_int(p.w);
+            // d = input - output, in binary64, no contraction
+            const double dx = SWAP ? __dsub_rn(cx, (double)p.x) : __dsub_rn((double)p.x, cx);
+            const double dy = SWAP ? __dsub_rn(cy, (double)p.y) : __dsub_rn((double)p.y, cy);
+            const double dz = SWAP ? __dsub_rn(cz, (double)p.z) : __dsub_rn((double)p.z, cz);
+            const double d2 = __dadd_rn(__dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy)), __dmul_rn(dz, dz));
+            hit = d2 <= q.r2;
+            const int tm1 = q.t - 1;
+            const double ux = floor(__dmul_rn(__dadd_rn(dx, q.R), q.inv_cell));
+            const double uy = floor(__dmul_rn(__dadd_rn(dy, q.R), q.inv_cell));
+            const double uz = floor(__dmul_rn(__dadd_rn(dz, q.R), q.inv_cell));
+            int kx = ux < 0.0 ? 0 : (int)fmin(ux, (double)tm1);
+            int ky = uy < 0.0 ? 0 : (int)fmin(uy, (double)tm1);
+            int kz = uz < 0.0 ? 0 : (int)fmin(uz, (double)tm1);
+            k = (kx * q.t + ky) * q.t + kz;
+        }
+        return hit;
+    }
+};
+
+// ---- pass 1: neighbours per (cell k, centre) --------------------------------------------------
+// One block per tile of TILE centres, one wave per centre at a time.
+//   tile_cnt   [n_tiles][K][TILE]   (may be NULL: totals only)
+//   tile_k_cnt [K * n_tiles]        k-major, input of the prefix sum
+template <bool SWAP>
+__global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__restrict__ centres, int64_t n_centres,
+                                                              GridView g, QueryParams q, int K, int64_t n_tiles,
+                                                              uint32_t *__restrict__ tile_cnt,
+                                                              uint32_t *__restrict__ tile_k_cnt)
+{
+    extern __shared__ uint32_t tbl[];          // [K][TILE]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tile = blockIdx.x;
+    for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
+    __syncthreads();
+    for (int al = wave; al < TILE; al += SEARCH_WAVES) {
+        const int64_t a = tile * TILE + al;
+        if (a >= n_centres) break;             // wave-uniform
+        Candidates<SWAP> c;
+        c.open(centres, a, g, lane);
+        for (uint32_t base = 0; base < c.total; base += 64) {
+            int b, k;
+            if (c.fetch(base + lane, g, q, b, k)) atomicAdd(&tbl[k * TILE + al], 1u);
+        }
+    }
+    __syncthreads();
+    if (tile_cnt) {
+        uint32_t *dst = tile_cnt + (size_t)tile * K * TILE;
+        for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) dst[idx] = tbl[idx];
+    }
+    for (int k = wave; k < K; k += SEARCH_WAVES) {
+        uint32_t v = tbl[k * TILE + lane];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+        if (lane == 0) tile_k_cnt[(size_t)k * n_tiles + tile] = v;
+    }
+}
+
+// ---- pass 2: write every triplet to its place in (k, centre, other) order ----------------------
+//   tile_ptr  [K * n_tiles + 1]  exclusive prefix sum of tile_k_cnt
+//   out_c / out_b / out_k: centre index, candidate index, cell of each triplet (any may be NULL)
+template <bool SWAP>
+__global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__restrict__ centres, int64_t n_centres,
+                                                             GridView g, QueryParams q, int K, int64_t n_tiles,
+                                                             const uint32_t *__restrict__ tile_cnt,
+                                                             const uint32_t *__restrict__ tile_ptr,
+                                                             int32_t *__restrict__ out_c, int32_t *__restrict__ out_b,
+                                                             int32_t *__restrict__ out_k, int list_cap)
+{
+    extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
+    __shared__ unsigned long long list_all[SEARCH_WAVES][LIST_CAP_MAX];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tile = blockIdx.x;
+    {
+        const uint32_t *src = tile_cnt + (size_t)tile * K * TILE;
+        for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = src[idx];
+    }
+    __syncthreads();
+    for (int k = wave; k < K; k += SEARCH_WAVES) {
+        const uint32_t v = tbl[k * TILE + lane];
+        const uint32_t inc = wave_incl_scan_u32(v, lane);
+        tbl[k * TILE + lane] = tile_ptr[(size_t)k * n_tiles + tile] + inc - v;
+    }
+    __syncthreads();
+    volatile unsigned long long *list = list_all[wave];
+    const unsigned long long lane_lt = (1ull << lane) - 1ull;
+    for (int al = wave; al < TILE; al += SEARCH_WAVES) {
+        const int64_t a = tile * TILE + al;
+        if (a >= n_centres) break;             // wave-uniform
+        Candidates<SWAP> c;
+        c.open(centres, a, g, lane);
+        // neighbours of this centre, compacted into the wave's list by ballot + prefix popcount
+        uint32_t n = 0;
+        for (uint32_t base = 0; base < c.total; base += 64) {
+            int b, k;
+            const bool hit = c.fetch(base + lane, g, q, b, k);
+            const unsigned long long m = __ballot(hit);
+            const uint32_t pos = n + (uint32_t)__popcll(m & lane_lt);
+            if (hit && pos < (uint32_t)list_cap) list[pos] = ((unsigned long long)(uint32_t)k << 32) | (uint32_t)b;
+            n += (uint32_t)__popcll(m);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (n <= (uint32_t)list_cap) {
+            // rank of each neighbour among those with the same cell and a smaller index
+            for (uint32_t e = lane; e < n; e += 64) {
+                const unsigned long long key = list[e];
+                const unsigned long long kbase = key & 0xffffffff00000000ull;
+                const unsigned long long rel = key - kbase;
+                uint32_t rank = 0;
+                for (uint32_t e2 = 0; e2 < n; ++e2) rank += ((list[e2] - kbase) < rel) ? 1u : 0u;
+                const int k = (int)(key >> 32);
+                const uint32_t pos = tbl[k * TILE + al] + rank;
+                if (out_c) out_c[pos] = (int32_t)a;
+                if (out_b) out_b[pos] = (int32_t)(uint32_t)key;
+                if (out_k) out_k[pos] = k;
+            }
+        } else {
+            // more neighbours than the list holds: rank each one by scanning the candidates again
+            for (uint32_t base = 0; base < c.total; base += 64) {
+                int b, k;
+                const bool hit = c.fetch(base + lane, g, q, b, k);
+                uint32_t rank = 0;
+                for (uint32_t idx2 = 0; idx2 < c.total; ++idx2) {
+                    int b2, k2;
+                    const bool hit2 = c.fetch(idx2, g, q, b2, k2);
+                    rank += (hit2 && k2 == k && b2 < b) ? 1u : 0u;
+                }
+                if (hit) {
+                    const uint32_t pos = tbl[k * TILE + al] + rank;
+                    if (out_c) out_c[pos] = (int32_t)a;
+                    if (out_b) out_b[pos] = b;
+                    if (out_k) out_k[pos] = k;
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+__global__ void seg_offsets_kernel(const uint32_t *__restrict__ tile_ptr, int K, int64_t n_tiles,
+                                   int64_t *__restrict__ seg_offsets)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k <= K) seg_offsets[k] = (int64_t)tile_ptr[(size_t)k * n_tiles];
+}
+
+// ---- host side ------------------------------------------------------------------------------
+
+struct GridScratch {
+    size_t keys_off, cnt_off, cursor_off, point_slot_off, pts_off, end;
+    int64_t slots;
+};
+
+int64_t grid_slots(int64_t n)
+{
+    int64_t s = 64;
+    while (s < 2 * n) s <<= 1;
+    return s;
+}
+
+GridScratch grid_scratch(size_t base, int64_t n)
+{
+    GridScratch s;
+    s.slots = grid_slots(n);
+    size_t off = base;
+    s.keys_off = off;        off += align_up((size_t)s.slots * 8);
+    s.cnt_off = off;         off += align_up((size_t)(s.slots + 1) * 4);
+    s.cursor_off = off;      off += align_up((size_t)s.slots * 4);
+    s.point_slot_off = off;  off += align_up((size_t)(n > 0 ? n : 1) * 4);
+    s.pts_off = off;         off += align_up((size_t)(n > 0 ? n : 1) * 16);
+    s.end = off;
+    return s;
+}
+
+struct BuildScratch {
+    GridScratch grid_in, grid_out;
+    size_t scan_off;                 // scratch of the prefix sums
+    size_t total_off;                // unsigned long long[2]
+    size_t fwd_ptr_off, fwd_cnt_off; // used when the caller gives no plan
+    size_t bwd_ptr_off, bwd_cnt_off;
+    size_t end;
+};
+
+BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K)
+{
+    BuildScratch b;
+    b.grid_in = grid_scratch(0, n_in);
+    b.grid_out = grid_scratch(b.grid_in.end, n_out);
+    size_t off = b.grid_out.end;
+    const int64_t nt_o = ceil_div(n_out, TILE), nt_i = ceil_div(n_in, TILE);
+    int64_t scan_n = b.grid_in.slots > b.grid_out.slots ? b.grid_in.slots : b.grid_out.slots;
+    if ((int64_t)K * nt_o > scan_n) scan_n = (int64_t)K * nt_o;
+    if ((int64_t)K * nt_i > scan_n) scan_n = (int64_t)K * nt_i;
+    b.scan_off = off;    off += scan_scratch_bytes(scan_n);
+    b.total_off = off;   off += 256;
+    b.fwd_ptr_off = off; off += align_up((size_t)(K * nt_o + 1) * 4);
+    b.fwd_cnt_off = off; off += align_up((size_t)(nt_o > 0 ? nt_o : 1) * K * TILE * 4);
+    b.bwd_ptr_off = off; off += align_up((size_t)(K * nt_i + 1) * 4);
+    b.bwd_cnt_off = off; off += align_up((size_t)(nt_i > 0 ? nt_i : 1) * K * TILE * 4);
+    b.end = off;
+    return b;
+}
+
+int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridScratch &gs, void *scan_scratch,
+               GridView *view, hipStream_t stream)
+{
+    auto *keys = reinterpret_cast<unsigned long long *>(ws + gs.keys_off);
+    auto *cnt = reinterpret_cast<uint32_t *>(ws + gs.cnt_off);
+    auto *cursor = reinterpret_cast<uint32_t *>(ws + gs.cursor_off);
+    auto *point_slot = reinterpret_cast<uint32_t *>(ws + gs.point_slot_off);
+    auto *pts = reinterpret_cast<float4 *>(ws + gs.pts_off);
+    int rc;
+    if ((rc = fill_u64(keys, EMPTY_KEY, gs.slots, stream)) != PCPP_OK) return rc;
+    if ((rc = fill_u32(cnt, 0u, gs.slots + 1, stream)) != PCPP_OK) return rc;
+    if ((rc = fill_u32(cursor, 0u, gs.slots, stream)) != PCPP_OK) return rc;
+    if (n > 0) {
+        const unsigned blocks = (unsigned)ceil_div(n, 256);
+        grid_insert<<<blocks, 256, 0, stream>>>(xyz, n, inv_g, keys, cnt, (uint32_t)(gs.slots - 1), point_slot);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
+    if ((rc = scan_exclusive_u32(cnt, cnt, gs.slots, scan_scratch, nullptr, stream)) != PCPP_OK) return rc;
+    if (n > 0) {
+        const unsigned blocks = (unsigned)ceil_div(n, 256);
+        grid_scatter<<<blocks, 256, 0, stream>>>(xyz, n, point_slot, cnt, cursor, pts);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
+    view->keys = keys;
+    view->slot_start = cnt;
+    view->pts = pts;
+    view->mask = (uint32_t)(gs.slots - 1);
+    view->inv_g = inv_g;
+    return PCPP_OK;
+}
+
+int g_list_cap = LIST_CAP_MAX;
+
+}  // namespace
+
+PlanLayout plan_layout(int64_t n_in, int64_t n_out, int K, int64_t n_triplets, int flags)
+{
+    PlanLayout p;
+    size_t off = 256;   // header
+    auto side = [&](SideLayout &s, int64_t n_centres, bool with_gather) {
+        s.n_centres = n_centres;
+        s.n_tiles = ceil_div(n_centres, TILE);
+        s.tile_ptr_off = off;  off += align_up((size_t)(K * s.n_tiles + 1) * 4);
+        s.tile_cnt_off = off;  off += align_up((size_t)(s.n_tiles > 0 ? s.n_tiles : 1) * K * TILE * 4);
+        s.gather_off = off;
+        if (with_gather) off += align_up((size_t)(n_triplets > 0 ? n_triplets : 1) * 4);
+        s.end = off;
+    };
+    if (flags & PCPP_PLAN_FWD) side(p.fwd, n_out, false);
+    if (flags & PCPP_PLAN_BWD_INPUT) side(p.bwd, n_in, true);
+    p.bytes = off;
+    return p;
+}
+
+}  // namespace pcpp
+
+using namespace pcpp;
+
+extern "C" {
+
+size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t)
+{
+    if (n_in < 0 || n_out < 0 || t < 1 || t > PCPP_MAX_T) return 0;
+    return build_scratch(n_in, n_out, t * t * t).end;
+}
+
+size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags)
+{
+    if (n_in < 0 || n_out < 0 || t < 1 || t > PCPP_MAX_T || n_triplets < 0) return 0;
+    return plan_layout(n_in, n_out, t * t * t, n_triplets, plan_flags).bytes;
+}
+
+// Test hook: number of neighbours of one centre the fill pass keeps on chip before it falls back to
+// ranking by a second scan of the candidates (1..1024).  Not part of the public contract.
+int pcpp_debug_set_list_cap(int cap)
+{
+    if (cap < 1 || cap > LIST_CAP_MAX) return PCPP_ERR_INVALID_ARG;
+    g_list_cap = cap;
+    return PCPP_OK;
+}
+
+int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz, int64_t n_out,
+                        float radius, int t,
+                        int32_t *tri_o, int32_t *tri_i, int32_t *tri_k, int64_t capacity,
+                        int64_t *seg_offsets, int64_t *n_triplets,
+                        void *plan, size_t plan_bytes, int plan_flags,
+                        void *workspace, size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (n_in < 0 || n_out < 0 || (n_in > 0 && !in_xyz) || (n_out > 0 && !out_xyz) || !n_triplets) {
+        set_error("pcpp_build_triplets: null pointer or negative size");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    if (n_in >= INT32_MAX || n_out >= INT32_MAX) {
+        set_error("pcpp_build_triplets: point counts must be below 2^31");
+        return PCPP_ERR_UNSUPPORTED;
+    }
+    if (!(radius > 0.0f) || !isfinite(radius)) {
+        set_error("pcpp_build_triplets: radius must be finite and positive");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    if (t < 1 || t > PCPP_MAX_T) {
+        set_error("pcpp_build_triplets: t must be in 1..%d", PCPP_MAX_T);
+        return PCPP_ERR_INVALID_ARG;
+    }
+    const int n_null = (tri_o == nullptr) + (tri_i == nullptr) + (tri_k == nullptr);
+    if (n_null != 0 && n_null != 3) {
+        set_error("pcpp_build_triplets: tri_o, tri_i, tri_k must be all NULL or all non-NULL");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    const bool count_only = n_null == 3;
+    if (!count_only && (capacity < 0 || !seg_offsets)) {
+        set_error("pcpp_build_triplets: seg_offsets is NULL or capacity negative");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    if (plan && ((plan_flags & ~(PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT)) || !(plan_flags & PCPP_PLAN_FWD))) {
+        set_error("pcpp_build_triplets: plan_flags must be PCPP_PLAN_FWD, optionally with PCPP_PLAN_BWD_INPUT");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    const int K = t * t * t;
+    const BuildScratch bs = build_scratch(n_in, n_out, K);
+    if (!workspace || workspace_bytes < bs.end || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
+        set_error("pcpp_build_triplets: workspace missing, misaligned or smaller than %zu bytes", bs.end);
+        return PCPP_ERR_WORKSPACE;
+    }
+    if (plan && (reinterpret_cast<uintptr_t>(plan) & 255)) {
+        set_error("pcpp_build_triplets: plan must be 256-byte aligned");
+        return PCPP_ERR_WORKSPACE;
+    }
+    *n_triplets = 0;
+    char *ws = static_cast<char *>(workspace);
+    void *scan_scratch = ws + bs.scan_off;
+    auto *total_dev = reinterpret_cast<unsigned long long *>(ws + bs.total_off);
+
+    // grid pitch a hair above r so that, with the binary64 cell computation, any accepted pair lies
+    // in adjacent grid cells (27-cell stencil is conservative)
+    const double R = (double)radius;
+    const double inv_g = 1.0 / (R * (1.0 + 1.0 / 1048576.0));
+    QueryParams q;
+    q.R = R;
+    q.r2 = R * R;
+    q.inv_cell = (double)t / (2.0 * R);
+    q.t = t;
+
+    int rc;
+    GridView grid_in;
+    if ((rc = build_grid(in_xyz, n_in, inv_g, ws, bs.grid_in, scan_scratch, &grid_in, stream)) != PCPP_OK) return rc;
+
+    const int64_t nt_o = ceil_div(n_out, TILE);
+    const size_t lds = (size_t)K * TILE * sizeof(uint32_t);
+    if (lds > (size_t)32 * 1024) {
+        // large t: the per-tile table plus the neighbour lists exceed the default dynamic LDS limit
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    const bool want_fwd_plan = plan && (plan_flags & PCPP_PLAN_FWD) && !count_only;
+    const bool want_bwd_plan = plan && (plan_flags & PCPP_PLAN_BWD_INPUT) && !count_only;
+
+    // forward side: centres = outputs, candidates = inputs.  Counts go to the workspace first; the
+    // plan layout depends on |T|, which is only known after the prefix sum.
+    uint32_t *f_ptr = reinterpret_cast<uint32_t *>(ws + bs.fwd_ptr_off);
+    uint32_t *f_cnt = reinterpret_cast<uint32_t *>(ws + bs.fwd_cnt_off);
+    if (nt_o > 0) {
+        query_count<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o,
+                                                                         count_only ? nullptr : f_cnt, f_ptr);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
+    if ((rc = scan_exclusive_u32(f_ptr, f_ptr, (int64_t)K * nt_o, scan_scratch, total_dev, stream)) != PCPP_OK) return rc;
+
+    unsigned long long total = 0;
+    PCPP_HIP_CHECK(hipMemcpyAsync(&total, total_dev, sizeof(total), hipMemcpyDeviceToHost, stream));
+    PCPP_HIP_CHECK(hipStreamSynchronize(stream));
+    *n_triplets = (int64_t)total;
+    if (total >= (unsigned long long)INT32_MAX) {
+        set_error("pcpp_build_triplets: %llu triplets; the library indexes at most 2^31-1", total);
+        return PCPP_ERR_UNSUPPORTED;
+    }
+    if (count_only) return PCPP_OK;
+    if ((int64_t)total > capacity) {
+        set_error("pcpp_build_triplets: %llu triplets but capacity is %lld", total, (long long)capacity);
+        return PCPP_ERR_CAPACITY;
+    }
+    PlanLayout pl;
+    if (plan) {
+        pl = plan_layout(n_in, n_out, K, (int64_t)total, plan_flags);
+        if (plan_bytes < pl.bytes) {
+            set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs %zu", plan_bytes, pl.bytes);
+            return PCPP_ERR_WORKSPACE;
+        }
+    }
+    if (nt_o > 0) {
+        query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
+                                                                        f_ptr, tri_o, tri_i, tri_k, g_list_cap);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
+    if (nt_o > 0) {
+        seg_offsets_kernel<<<(K + 1 + 63) / 64, 64, 0, stream>>>(f_ptr, K, nt_o, seg_offsets);
+        PCPP_HIP_CHECK(hipGetLastError());
+    } else {
+        // no outputs: every run starts at 0
+        PCPP_HIP_CHECK(hipMemsetAsync(seg_offsets, 0, (size_t)(K + 1) * sizeof(int64_t), stream));
+    }
+    char *pb = static_cast<char *>(plan);
+    if (want_fwd_plan) {
+        PCPP_HIP_CHECK(hipMemcpyAsync(pb + pl.fwd.tile_ptr_off, f_ptr, (size_t)(K * nt_o + 1) * 4,
+                                      hipMemcpyDeviceToDevice, stream));
+        if (nt_o > 0)
+            PCPP_HIP_CHECK(hipMemcpyAsync(pb + pl.fwd.tile_cnt_off, f_cnt, (size_t)nt_o * K * TILE * 4,
+                                          hipMemcpyDeviceToDevice, stream));
+    }
+    if (want_bwd_plan) {
+        // input-gradient side: centres = inputs, candidates = outputs; same predicate with the roles
+        // swapped, so the set is identical and only the grouping changes to (k, i, o)
+        const int64_t nt_i = ceil_div(n_in, TILE);
+        GridView grid_out;
+        if (out_xyz == in_xyz && n_out == n_in) {
+            grid_out = grid_in;
+        } else {
+            if ((rc = build_grid(out_xyz, n_out, inv_g, ws, bs.grid_out, scan_scratch, &grid_out, stream)) != PCPP_OK)
+                return rc;
+        }
+        uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
+        uint32_t *b_cnt = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_cnt_off);
+        int32_t *b_gather = reinterpret_cast<int32_t *>(pb + pl.bwd.gather_off);
+        if (nt_i > 0) {
+            query_count<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
+                                                                            b_ptr);
+            PCPP_HIP_CHECK(hipGetLastError());
+        }
+        if ((rc = scan_exclusive_u32(b_ptr, b_ptr, (int64_t)K * nt_i, scan_scratch, total_dev + 1, stream)) != PCPP_OK)
+            return rc;
+        if (nt_i > 0) {
+            query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
+                                                                           b_ptr, nullptr, b_gather, nullptr,
+                                                                           g_list_cap);
+            PCPP_HIP_CHECK(hipGetLastError());
+        }
+    }
+    return PCPP_OK;
+}
+
+}  // extern "C"

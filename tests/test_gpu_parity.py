@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import scenes
+from parity_util import TOL, assert_close, oracle_bwd_input, oracle_bwd_weight, oracle_fwd
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pcpp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2511_23227_amd as m
+    m.library()
+    return m
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(dtype) if dtype is not None else t
+
+
+def feat_dtype(scene):
+    return torch.bfloat16 if scene.dtype == "bf16" else torch.float32
+
+
+def build_gpu(pcpp, in_xyz, out_xyz, r, t, same=False):
+    din = dev(in_xyz)
+    dout = din if same else dev(out_xyz)
+    return pcpp.pcpp_build_triplets(din, dout, r, t)
+
+
+def check_triplets(T, o, i, k, seg):
+    assert T.n_triplets == len(o)
+    assert np.array_equal(T.seg_offsets.cpu().numpy(), seg)
+    assert np.array_equal(T.tri_k.cpu().numpy(), k)
+    assert np.array_equal(T.tri_o.cpu().numpy(), o)
+    assert np.array_equal(T.tri_i.cpu().numpy(), i)
+
+
+def run_ops(pcpp, scene, T, x, w, dy, o, i, k, ops):
+    tol = TOL[scene.dtype]
+    dt = feat_dtype(scene)
+    dx_, dw_, ddy = dev(x, dt), dev(w, dt), dev(dy, dt)
+    if "fwd" in ops:
+        out = pcpp.pcpp_mvmr_fwd(dx_, dw_, T).cpu().numpy()
+        ref, scale = oracle_fwd(x, w, o, i, k, scene.n_out)
+        assert_close(out, ref, scale, tol, f"{scene.name} fwd")
+    if "bwd_input" in ops:
+        gx = pcpp.pcpp_mvmr_bwd_input(ddy, dw_, T).cpu().numpy()
+        ref, scale = oracle_bwd_input(dy, w, o, i, k, scene.n_in)
+        assert_close(gx, ref, scale, tol, f"{scene.name} bwd_input")
+    if "bwd_weight" in ops:
+        gw = pcpp.pcpp_mvmr_bwd_weight(dx_, ddy, T).cpu().numpy()
+        ref, scale = oracle_bwd_weight(x, dy, o, i, k, scene.K)
+        assert_close(gw, ref, scale, tol, f"{scene.name} bwd_weight")
+        assert not gw[np.diff(T.seg_offsets.cpu().numpy()) == 0].any()      # unused cells: exact zeros
+
+
+@pytest.mark.parametrize("sid", [1, 2])
+def test_scene_full(pcpp, sid):
+    """Scenes 1-2 at full size: triplets bit-exact, every op within tolerance on every element."""
+    s = scenes.make_scene(sid)
+    x, w, dy = scenes.make_features(s)
+    o, i, k, seg = oracle.build_triplets(s.in_xyz, s.out_xyz, s.radius, s.t)
+    T = build_gpu(pcpp, s.in_xyz, s.out_xyz, s.radius, s.t, same=True)
+    check_triplets(T, o, i, k, seg)
+    run_ops(pcpp, s, T, x, w, dy, o, i, k, ("fwd", "bwd_input", "bwd_weight"))
+
+
+@pytest.mark.parametrize("case", [
+    dict(n_in=700, n_out=333, r=0.17, t=3, cin=5, cout=7, dt="f32"),
+    dict(n_in=1000, n_out=1000, r=0.12, t=2, cin=24, cout=8, dt="bf16"),
+    dict(n_in=900, n_out=129, r=0.2, t=5, cin=70, cout=33, dt="f32"),
+    dict(n_in=64, n_out=64, r=0.5, t=1, cin=3, cout=3, dt="f32"),
+    dict(n_in=300, n_out=2000, r=0.15, t=4, cin=16, cout=130, dt="bf16"),
+])
+def test_small_shapes(pcpp, case):
+    """Ragged sizes: n_out != n_in, partial tiles, channel counts that are not multiples of anything."""
+    rng = np.random.default_rng(hash(tuple(sorted(case.items()))) & 0xffff)
+    pin = rng.uniform(0, 1, (case["n_in"], 3)).astype(np.float32)
+    pout = rng.uniform(0, 1, (case["n_out"], 3)).astype(np.float32)
+    K = case["t"] ** 3
+    x = rng.standard_normal((case["n_in"], case["cin"])).astype(np.float32)
+    w = (rng.standard_normal((K, case["cout"], case["cin"])) / np.sqrt(K * case["cin"])).astype(np.float32)
+    dy = rng.standard_normal((case["n_out"], case["cout"])).astype(np.float32)
+    if case["dt"] == "bf16":
+        x, w, dy = scenes.round_to_bf16(x), scenes.round_to_bf16(w), scenes.round_to_bf16(dy)
+    s = scenes.Scene(0, "small", pin, pout, float(np.float32(case["r"])), case["t"], case["cin"], case["cout"], case["dt"])
+    o, i, k, seg = oracle.build_triplets(pin, pout, s.radius, s.t)
+    T = build_gpu(pcpp, pin, pout, s.radius, s.t)
+    check_triplets(T, o, i, k, seg)
+    run_ops(pcpp, s, T, x, w, dy, o, i, k, ("fwd", "bwd_input", "bwd_weight"))
+
+
+def test_edge_cases(pcpp):
+    m = pcpp
+    # no inputs, some outputs: zero triplets, zero output rows
+    pin = np.zeros((0, 3), np.float32)
+    pout = np.random.default_rng(0).uniform(0, 1, (10, 3)).astype(np.float32)
+    T = build_gpu(m, pin, pout, 0.3, 3)
+    assert T.n_triplets == 0 and not T.seg_offsets.cpu().numpy().any()
+    out = m.pcpp_mvmr_fwd(torch.zeros((0, 4), device="cuda"), torch.ones((27, 6, 4), device="cuda"), T)
+    assert out.shape == (10, 6) and not out.cpu().numpy().any()
+    # no outputs
+    T = build_gpu(m, pout, pin, 0.3, 3)
+    assert T.n_triplets == 0
+    # coincident points: every pair is a triplet in the centre cell
+    q = np.tile(np.array([[0.25, 0.5, 0.75]], np.float32), (70, 1))
+    T = build_gpu(m, q, q, 0.1, 3, same=True)
+    o, i, k, seg = oracle.build_triplets(q, q, np.float32(0.1), 3)
+    check_triplets(T, o, i, k, seg)
+    assert T.n_triplets == 4900 and np.all(k == 13)
+    # far-apart points: only self pairs; outputs with no neighbour give zero rows
+    far = (np.arange(30, dtype=np.float32)[:, None] * np.array([[10.0, 0, 0]], np.float32))
+    T = build_gpu(m, far[:20], far, 0.5, 3)
+    o, i, k, seg = oracle.build_triplets(far[:20], far, np.float32(0.5), 3)
+    check_triplets(T, o, i, k, seg)
+    x = torch.ones((20, 2), device="cuda")
+    out = m.pcpp_mvmr_fwd(x, torch.ones((27, 2, 2), device="cuda"), T).cpu().numpy()
+    assert np.array_equal(out[:20], np.full((20, 2), 2.0)) and not out[20:].any()
+
+
+def test_boundary_ties_and_large_coordinates(pcpp):
+    """Points on a coarse binary grid produce exact ties at |d| = r and on cell faces."""
+    rng = np.random.default_rng(9)
+    p = (rng.integers(0, 64, (3000, 3)) / 16.0).astype(np.float32)          # spacing 1/16
+    for shift in (0.0, 4096.0):
+        q = (p + np.float32(shift)).astype(np.float32)
+        for r, t in ((0.25, 4), (0.1875, 3), (0.3125, 5)):
+            o, i, k, seg = oracle.build_triplets(q, q, np.float32(r), t)
+            T = build_gpu(pcpp, q, q, r, t, same=True)
+            check_triplets(T, o, i, k, seg)
+
+
+def test_dense_cluster_uses_rescan_path(pcpp):
+    """More neighbours per centre than the on-chip list holds: ranks come from a second scan."""
+    rng = np.random.default_rng(4)
+    p = rng.normal(0.5, 0.02, (1500, 3)).astype(np.float32)
+    o, i, k, seg = oracle.build_triplets(p, p, np.float32(0.05), 3)
+    L = pcpp.library()
+    assert L.pcpp_debug_set_list_cap(40) == 0
+    try:
+        T = build_gpu(pcpp, p, p, 0.05, 3, same=True)
+    finally:
+        assert L.pcpp_debug_set_list_cap(1024) == 0
+    assert np.bincount(o).max() > 40
+    check_triplets(T, o, i, k, seg)
+
+
+def test_error_paths(pcpp):
+    m = pcpp
+    p = dev(np.random.default_rng(1).uniform(0, 1, (500, 3)).astype(np.float32))
+    n = m.binding.pcpp_count_triplets(p, p, 0.2, 3)
+    assert n == oracle.count_triplets(p.cpu().numpy(), p.cpu().numpy(), np.float32(0.2), 3)
+    with pytest.raises(m.PcppError) as e:
+        m.pcpp_build_triplets(p, p, 0.2, 3, capacity=n - 1)
+    assert e.value.code == -2 and str(n) in str(e.value)
+    with pytest.raises(m.PcppError) as e:
+        m.pcpp_build_triplets(p, p, -1.0, 3)
+    assert e.value.code == -1
+    with pytest.raises(m.PcppError):
+        m.pcpp_build_triplets(p, p, 0.2, 9)
+    T = m.pcpp_build_triplets(p, p, 0.2, 3, plan_flags=m.PLAN_FWD)
+    with pytest.raises(m.PcppError):
+        m.pcpp_mvmr_bwd_input(torch.zeros((500, 4), device="cuda"), torch.zeros((27, 4, 4), device="cuda"), T)
+
+
+def test_determinism(pcpp):
+    """Two runs give identical triplet arrays and identical float bits (no atomics on the data path)."""
+    s = scenes.make_scene(1)
+    x, w, dy = scenes.make_features(s)
+    outs = []
+    for _ in range(2):
+        T = build_gpu(pcpp, s.in_xyz, s.out_xyz, s.radius, s.t, same=True)
+        out = pcpp.pcpp_mvmr_fwd(dev(x), dev(w), T)
+        gx = pcpp.pcpp_mvmr_bwd_input(dev(dy), dev(w), T)
+        gw = pcpp.pcpp_mvmr_bwd_weight(dev(x), dev(dy), T)
+        outs.append([T.tri_o.cpu().numpy(), T.tri_i.cpu().numpy(), T.tri_k.cpu().numpy(), out.cpu().numpy(),
+                     gx.cpu().numpy(), gw.cpu().numpy()])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
