@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the PointCNN++ MVMR hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic scene already resident in HBM:
+pcpp_build_triplets (hashed-grid search + reorder) -> pcpp_mvmr_fwd -> pcpp_mvmr_bwd_input ->
+pcpp_mvmr_bwd_weight.  The headline value is neighbour pairs per second = |T| / step time.
+One JSON line is printed; it also carries the per-op times, the roofline of the dominant MVMR
+kernel (algorithmic bytes over the kernel time measured with events on the launch stream) and the
+CPU oracle timed on the host cores (cpu_baseline).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
+# (scene, order, op); absent entries are reported as null.
+MEASURED_TRAFFIC: dict = {}
+
+
+def algorithmic_bytes(op: str, n_t: int, n_in: int, n_out: int, c_in: int, c_out: int, K: int, s_in: int,
+                      s_out: int) -> float:
+    """Bytes the method itself has to move per launch (Eq. (3) of Sec. 3.3.2 with W read once):
+    every triplet fetches one source row and its two int32 indices, every destination row is
+    written once, W is read once."""
+    if op == "fwd":
+        return n_t * (c_in * s_in + 8) + n_out * c_out * s_out + K * c_in * c_out * s_in
+    if op == "bwd_input":
+        return n_t * (c_out * s_in + 8) + n_in * c_in * s_out + K * c_in * c_out * s_in
+    if op == "bwd_weight":
+        return n_t * ((c_in + c_out) * s_in + 8) + K * c_in * c_out * 4
+    raise ValueError(op)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--scene", type=int, default=2, help="synthetic scene id (default 2: the headline workload)")
+    ap.add_argument("--order", default="default", choices=["default", "morton"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU only (the paper's operator is a one-GPU kernel); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2511_23227_amd as pcpp
+    import scenes
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    pcpp.library()
+
+    s = scenes.make_scene(args.scene, order=args.order)
+    x, w, dy = scenes.make_features(s)
+    fdt = torch.bfloat16 if s.dtype == "bf16" else torch.float32
+    s_in = 2 if s.dtype == "bf16" else 4
+    in_xyz = torch.from_numpy(s.in_xyz).cuda()
+    out_xyz = in_xyz if s.out_xyz is s.in_xyz else torch.from_numpy(s.out_xyz).cuda()
+    dx_, dw_, ddy = (torch.from_numpy(a).cuda().to(fdt) for a in (x, w, dy))
+    ops = [op for op in ("fwd", "bwd_input", "bwd_weight") if op in s.ops]
+    flags = pcpp.PLAN_FWD | (pcpp.PLAN_BWD_INPUT if "bwd_input" in ops else 0)
+
+    # persistent caller-owned buffers, sized once outside the timed region
+    T0 = pcpp.pcpp_build_triplets(in_xyz, out_xyz, s.radius, s.t, plan_flags=flags)
+    n_t = T0.n_triplets
+    L = pcpp.library()
+    code = 1 if s.dtype == "bf16" else 0
+    buffers = dict(tri_o=torch.empty(n_t, dtype=torch.int32, device="cuda"),
+                   tri_i=torch.empty(n_t, dtype=torch.int32, device="cuda"),
+                   tri_k=torch.empty(n_t, dtype=torch.int32, device="cuda"),
+                   seg_offsets=torch.empty(s.K + 1, dtype=torch.int64, device="cuda"),
+                   plan=torch.empty(L.pcpp_plan_bytes(s.n_in, s.n_out, s.t, n_t, flags), dtype=torch.uint8, device="cuda"),
+                   workspace=torch.empty(L.pcpp_build_triplets_workspace_bytes(s.n_in, s.n_out, s.t),
+                                         dtype=torch.uint8, device="cuda"))
+    ws = {i_: torch.empty(max(256, L.pcpp_mvmr_workspace_bytes(i_, s.n_in, s.n_out, s.c_in, s.c_out, s.K, code)),
+                          dtype=torch.uint8, device="cuda") for i_ in range(3)}
+    out = torch.empty((s.n_out, s.c_out), dtype=torch.float32, device="cuda")
+    gx = torch.empty((s.n_in, s.c_in), dtype=torch.float32, device="cuda")
+    gw = torch.empty((s.K, s.c_out, s.c_in), dtype=torch.float32, device="cuda")
+    del T0
+
+    names = ["build"] + ops
+    events = []
+
+    def step(record: bool):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] if record else None
+        if record:
+            ev[0].record()
+        T = pcpp.pcpp_build_triplets(in_xyz, out_xyz, s.radius, s.t, plan_flags=flags, capacity=n_t, buffers=buffers)
+        j = 1
+        if record:
+            ev[j].record()
+        if "fwd" in ops:
+            pcpp.pcpp_mvmr_fwd(dx_, dw_, T, out=out, workspace=ws[0]); j += 1
+            if record:
+                ev[j].record()
+        if "bwd_input" in ops:
+            pcpp.pcpp_mvmr_bwd_input(ddy, dw_, T, dx=gx, workspace=ws[1]); j += 1
+            if record:
+                ev[j].record()
+        if "bwd_weight" in ops:
+            pcpp.pcpp_mvmr_bwd_weight(dx_, ddy, T, dw=gw, workspace=ws[2]); j += 1
+            if record:
+                ev[j].record()
+        if record:
+            events.append(ev)
+        return T
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        T = step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert T.n_triplets == n_t
+
+    op_ms = {nm: float(np.mean([ev[j].elapsed_time(ev[j + 1]) for ev in events])) for j, nm in enumerate(names)}
+
+    def roofline(op):
+        b = algorithmic_bytes(op, n_t, s.n_in, s.n_out, s.c_in, s.c_out, s.K, s_in, 4)
+        gbs = b / (op_ms[op] * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((args.scene, args.order, op)),
+                "kernel": op, "algorithmic_bytes": int(b), "ms": round(op_ms[op], 4),
+                "nominal_tflops": round(2.0 * n_t * s.c_in * s.c_out / (op_ms[op] * 1e-3) / 1e12, 2)}
+
+    per_op = {op: roofline(op) for op in ops}
+    dominant = max(ops, key=lambda o_: op_ms[o_])
+
+    result = {
+        "metric": "MVMR fwd+bwd neighbour-pairs/s (whole hot path: triplet build + fwd + bwd_input + bwd_weight)",
+        "value": round(n_t / (ms_per_step * 1e-3), 1),
+        "unit": "pairs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": s.dtype, "data": "synthetic",
+        "config": {"workload": f"scene{s.scene_id}_{s.name}", "order": args.order, "n_in": s.n_in, "n_out": s.n_out,
+                   "radius": s.radius, "t": s.t, "c_in": s.c_in, "c_out": s.c_out, "n_triplets": n_t,
+                   "ops": names},
+        "op_ms": {k_: round(v, 4) for k_, v in op_ms.items()},
+        "pairs_per_s": {k_: round(n_t / (v * 1e-3), 1) for k_, v in op_ms.items()},
+        "roofline": per_op[dominant],
+        "roofline_per_op": per_op,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample of the same workload: the first n_sample outputs against all inputs
+        n_sample = min(s.n_out, max(1024, int(2.0e9 / max(s.n_in, 1))))
+        sub = np.ascontiguousarray(s.out_xyz[:n_sample])
+        c0 = time.perf_counter()
+        o, i, k, seg = oracle.build_triplets(s.in_xyz, sub, s.radius, s.t)
+        c1 = time.perf_counter()
+        oracle.mvmr_fwd(x, w, o, i, k, n_sample)
+        if "bwd_input" in ops:
+            oracle.mvmr_bwd_input(dy[:n_sample], w, o, i, k, s.n_in)
+        if "bwd_weight" in ops:
+            oracle.mvmr_bwd_weight(x, dy[:n_sample], o, i, k, s.K)
+        c2 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": round(len(o) / (c2 - c0), 1), "unit": "pairs/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"first {n_sample} of {s.n_out} outputs against all {s.n_in} inputs: {len(o)} triplets; "
+                      f"brute-force search {c1 - c0:.2f} s, {'+'.join(ops)} {c2 - c1:.2f} s"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -226,7 +226,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
                                                              const uint32_t *__restrict__ tile_cnt,
                                                              const uint32_t *__restrict__ tile_ptr,
                                                              int32_t *__restrict__ out_c, int32_t *__restrict__ out_b,
-                                                             int32_t *__restrict__ out_k, int list_cap)
+                                                             int32_t *__restrict__ out_k,
+                                                             uint32_t *__restrict__ run_start_out, int list_cap)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
     __shared__ unsigned long long list_all[SEARCH_WAVES][LIST_CAP_MAX];
@@ -243,6 +244,10 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
         tbl[k * TILE + lane] = tile_ptr[(size_t)k * n_tiles + tile] + inc - v;
     }
     __syncthreads();
+    if (run_start_out) {
+        uint32_t *dst = run_start_out + (size_t)tile * K * TILE;
+        for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) dst[idx] = tbl[idx];
+    }
     volatile unsigned long long *list = list_all[wave];
     const unsigned long long lane_lt = (1ull << lane) - 1ull;
     for (int al = wave; al < TILE; al += SEARCH_WAVES) {
@@ -405,7 +410,7 @@ PlanLayout plan_layout(int64_t n_in, int64_t n_out, int K, int64_t n_triplets, i
         s.n_centres = n_centres;
         s.n_tiles = ceil_div(n_centres, TILE);
         s.tile_ptr_off = off;  off += align_up((size_t)(K * s.n_tiles + 1) * 4);
-        s.tile_cnt_off = off;  off += align_up((size_t)(s.n_tiles > 0 ? s.n_tiles : 1) * K * TILE * 4);
+        s.run_start_off = off; off += align_up((size_t)(s.n_tiles > 0 ? s.n_tiles : 1) * K * TILE * 4);
         s.gather_off = off;
         if (with_gather) off += align_up((size_t)(n_triplets > 0 ? n_triplets : 1) * 4);
         s.end = off;
@@ -558,9 +563,12 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
             return PCPP_ERR_WORKSPACE;
         }
     }
+    char *pb = static_cast<char *>(plan);
     if (nt_o > 0) {
+        uint32_t *f_runs = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
         query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
-                                                                        f_ptr, tri_o, tri_i, tri_k, g_list_cap);
+                                                                        f_ptr, tri_o, tri_i, tri_k, f_runs,
+                                                                        g_list_cap);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if (nt_o > 0) {
@@ -570,13 +578,9 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         // no outputs: every run starts at 0
         PCPP_HIP_CHECK(hipMemsetAsync(seg_offsets, 0, (size_t)(K + 1) * sizeof(int64_t), stream));
     }
-    char *pb = static_cast<char *>(plan);
     if (want_fwd_plan) {
         PCPP_HIP_CHECK(hipMemcpyAsync(pb + pl.fwd.tile_ptr_off, f_ptr, (size_t)(K * nt_o + 1) * 4,
                                       hipMemcpyDeviceToDevice, stream));
-        if (nt_o > 0)
-            PCPP_HIP_CHECK(hipMemcpyAsync(pb + pl.fwd.tile_cnt_off, f_cnt, (size_t)nt_o * K * TILE * 4,
-                                          hipMemcpyDeviceToDevice, stream));
     }
     if (want_bwd_plan) {
         // input-gradient side: centres = inputs, candidates = outputs; same predicate with the roles
@@ -590,7 +594,8 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
                 return rc;
         }
         uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
-        uint32_t *b_cnt = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_cnt_off);
+        uint32_t *b_cnt = reinterpret_cast<uint32_t *>(ws + bs.bwd_cnt_off);
+        uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
         int32_t *b_gather = reinterpret_cast<int32_t *>(pb + pl.bwd.gather_off);
         if (nt_i > 0) {
             query_count<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
@@ -601,7 +606,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
             return rc;
         if (nt_i > 0) {
             query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
-                                                                           b_ptr, nullptr, b_gather, nullptr,
+                                                                           b_ptr, nullptr, b_gather, nullptr, b_runs,
                                                                            g_list_cap);
             PCPP_HIP_CHECK(hipGetLastError());
         }

@@ -33,22 +33,18 @@ template <typename T> __device__ inline float load_f(const T *p, size_t idx);
 template <> __device__ inline float load_f<float>(const float *p, size_t idx) { return p[idx]; }
 template <> __device__ inline float load_f<uint16_t>(const uint16_t *p, size_t idx) { return bf16_to_f32(p[idx]); }
 
-// Start of each centre's run inside the (k, tile) run, from the plan's counts.  Called by the whole
-// block; the results are visible after the next __syncthreads().
-__device__ inline void stage_runs(const PlanSideView &side, int K, int64_t tile, int k, uint32_t run_begin,
+// Start and length of each centre's run inside the (k, tile) run [run_begin, run_end), from the plan.
+// Called by the whole block; the results are visible after the next __syncthreads().
+__device__ inline void stage_runs(const PlanSideView &side, int K, int64_t tile, int k, uint32_t run_end,
                                   uint32_t *row_start, uint32_t *row_cnt)
 {
     if (threadIdx.x < TILE) {
         const int lane = threadIdx.x;
-        const uint32_t c = side.tile_cnt[((size_t)tile * K + k) * TILE + lane];
-        uint32_t inc = c;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint32_t u = __shfl_up(inc, d, 64);
-            if (lane >= d) inc += u;
-        }
-        row_cnt[lane] = c;
-        row_start[lane] = run_begin + inc - c;
+        const uint32_t *rs = side.run_start + ((size_t)tile * K + k) * TILE;
+        const uint32_t st = rs[lane];
+        const uint32_t en = lane < TILE - 1 ? rs[lane + 1] : run_end;
+        row_cnt[lane] = en - st;
+        row_start[lane] = st;
     }
 }
 
@@ -96,7 +92,7 @@ __global__ __launch_bounds__(THREADS) void rows_kernel(const TIn *__restrict__ f
         const uint32_t b = side.tile_ptr[(size_t)k * side.n_tiles + tile + 1];
         if (a == b) continue;                                  // block-uniform
         __syncthreads();
-        stage_runs(side, K, tile, k, a, row_start, row_cnt);
+        stage_runs(side, K, tile, k, b, row_start, row_cnt);
         for (int c0 = 0; c0 < c_src; c0 += CH) {
             __syncthreads();
             presum_chunk<TIn>(feat, c_src, c0, gather, row_start, row_cnt, S);
@@ -161,7 +157,7 @@ __global__ __launch_bounds__(THREADS) void weight_kernel(const T *__restrict__ f
         const uint32_t b = side.tile_ptr[(size_t)k * side.n_tiles + tile + 1];
         if (a == b) continue;                                  // block-uniform
         __syncthreads();
-        stage_runs(side, K, tile, k, a, row_start, row_cnt);
+        stage_runs(side, K, tile, k, b, row_start, row_cnt);
         __syncthreads();
         presum_chunk<T>(feat, c_in, ci0, gather, row_start, row_cnt, S);
         {

@@ -79,7 +79,7 @@ PlanSideView side_view(const void *plan, const SideLayout &s)
     const char *pb = static_cast<const char *>(plan);
     PlanSideView v;
     v.tile_ptr = reinterpret_cast<const uint32_t *>(pb + s.tile_ptr_off);
-    v.tile_cnt = reinterpret_cast<const uint32_t *>(pb + s.tile_cnt_off);
+    v.run_start = reinterpret_cast<const uint32_t *>(pb + s.run_start_off);
     v.gather = reinterpret_cast<const int32_t *>(pb + s.gather_off);
     v.n_tiles = s.n_tiles;
     return v;

@@ -33,14 +33,16 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // weight-gradient side, inputs for the input-gradient side).
 //   tile_ptr  uint32 [K * n_tiles + 1]  start of the (cell k, tile) run in the side's triplet
 //                                       order, k-major; last entry = |T|
-//   tile_cnt  uint32 [n_tiles][K][TILE] neighbours of centre tile*TILE + a in cell k
+//   run_start uint32 [n_tiles][K][TILE] start of the (cell k, centre tile*TILE + a) run; it ends where
+//                                       the next centre's run starts (for a = TILE-1: at the end of
+//                                       the (k, tile) run)
 //   gather    int32  [|T|]              (input-gradient side only) output index of each triplet in
 //                                       (k, i, o) order; the forward side gathers through tri_i
 struct SideLayout {
     int64_t n_centres = 0;
     int64_t n_tiles = 0;
     size_t tile_ptr_off = 0;
-    size_t tile_cnt_off = 0;
+    size_t run_start_off = 0;
     size_t gather_off = 0;
     size_t end = 0;
 };
@@ -55,7 +57,7 @@ PlanLayout plan_layout(int64_t n_in, int64_t n_out, int K, int64_t n_triplets, i
 
 struct PlanSideView {
     const uint32_t *tile_ptr;
-    const uint32_t *tile_cnt;
+    const uint32_t *run_start;
     const int32_t *gather;
     int64_t n_tiles;
 };

@@ -61,13 +61,13 @@ def run_ops(pcpp, scene, T, x, w, dy, o, i, k, ops):
         assert not gw[np.diff(T.seg_offsets.cpu().numpy()) == 0].any()      # unused cells: exact zeros
 
 
-@pytest.mark.parametrize("sid", [1, 2])
+@pytest.mark.parametrize("sid", [1, 2, 3, 4])
 def test_scene_full(pcpp, sid):
-    """Scenes 1-2 at full size: triplets bit-exact, every op within tolerance on every element."""
+    """Scenes 1-4 at full size: triplets bit-exact, every op within tolerance on every element."""
     s = scenes.make_scene(sid)
     x, w, dy = scenes.make_features(s)
     o, i, k, seg = oracle.build_triplets(s.in_xyz, s.out_xyz, s.radius, s.t)
-    T = build_gpu(pcpp, s.in_xyz, s.out_xyz, s.radius, s.t, same=True)
+    T = build_gpu(pcpp, s.in_xyz, s.out_xyz, s.radius, s.t, same=s.out_xyz is s.in_xyz)
     check_triplets(T, o, i, k, seg)
     run_ops(pcpp, s, T, x, w, dy, o, i, k, ("fwd", "bwd_input", "bwd_weight"))
 
@@ -78,6 +78,12 @@ def test_scene_full(pcpp, sid):
     dict(n_in=900, n_out=129, r=0.2, t=5, cin=70, cout=33, dt="f32"),
     dict(n_in=64, n_out=64, r=0.5, t=1, cin=3, cout=3, dt="f32"),
     dict(n_in=300, n_out=2000, r=0.15, t=4, cin=16, cout=130, dt="bf16"),
+    # shapes served by the matrix-core kernels, with ragged point counts
+    dict(n_in=1501, n_out=1333, r=0.12, t=3, cin=32, cout=32, dt="f32"),
+    dict(n_in=1300, n_out=1501, r=0.12, t=3, cin=64, cout=64, dt="bf16"),
+    dict(n_in=2100, n_out=700, r=0.15, t=3, cin=64, cout=128, dt="bf16"),
+    dict(n_in=999, n_out=999, r=0.2, t=5, cin=32, cout=32, dt="bf16"),
+    dict(n_in=800, n_out=31, r=0.2, t=2, cin=64, cout=64, dt="f32"),
 ])
 def test_small_shapes(pcpp, case):
     """Ragged sizes: n_out != n_in, partial tiles, channel counts that are not multiples of anything."""
