@@ -88,7 +88,7 @@ def main() -> int:
                    plan=torch.empty(L.pcpp_plan_bytes(s.n_in, s.n_out, s.t, n_t, flags), dtype=torch.uint8, device="cuda"),
                    workspace=torch.empty(L.pcpp_build_triplets_workspace_bytes(s.n_in, s.n_out, s.t),
                                          dtype=torch.uint8, device="cuda"))
-    ws = {i_: torch.empty(max(256, L.pcpp_mvmr_workspace_bytes(i_, s.n_in, s.n_out, s.c_in, s.c_out, s.K, code)),
+    ws = {i_: torch.empty(max(256, L.pcpp_mvmr_workspace_bytes(i_, s.n_in, s.n_out, n_t, s.c_in, s.c_out, s.K, code)),
                           dtype=torch.uint8, device="cuda") for i_ in range(3)}
     out = torch.empty((s.n_out, s.c_out), dtype=torch.float32, device="cuda")
     gx = torch.empty((s.n_in, s.c_in), dtype=torch.float32, device="cuda")

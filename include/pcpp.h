@@ -97,7 +97,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in,
  * Errors: INVALID_ARG, WORKSPACE, UNSUPPORTED (c_in or c_out < 1 or > 1024, dtype combination).
  * ------------------------------------------------------------------------------------------- */
 size_t pcpp_mvmr_workspace_bytes(int op /*0 fwd, 1 bwd_input, 2 bwd_weight*/, int64_t n_in, int64_t n_out,
-                                 int c_in, int c_out, int K, int in_dtype);
+                                 int64_t n_triplets, int c_in, int c_out, int K, int in_dtype);
 
 int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out_dtype,
                   int64_t n_in, int64_t n_out, int c_in, int c_out, int K,

@@ -49,7 +49,7 @@ def library() -> ctypes.CDLL:
     L.pcpp_build_triplets.argtypes = [vp, i64, vp, i64, f32, i32, vp, vp, vp, i64, vp,
                                       ctypes.POINTER(i64), vp, sz, i32, vp, sz, vp]
     L.pcpp_mvmr_workspace_bytes.restype = sz
-    L.pcpp_mvmr_workspace_bytes.argtypes = [i32, i64, i64, i32, i32, i32, i32]
+    L.pcpp_mvmr_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
     tail = [i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     L.pcpp_mvmr_fwd.restype = i32
     L.pcpp_mvmr_fwd.argtypes = [vp, vp, vp, i32, i32] + tail
@@ -171,7 +171,7 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
 
 
 def _mvmr_ws(op, T: Triplets, c_in, c_out, code, dev, workspace):
-    need = library().pcpp_mvmr_workspace_bytes(op, T.n_in, T.n_out, c_in, c_out, T.K, code)
+    need = library().pcpp_mvmr_workspace_bytes(op, T.n_in, T.n_out, T.n_triplets, c_in, c_out, T.K, code)
     if workspace is None or workspace.numel() < need:
         workspace = _bytes(need, dev)
     return workspace

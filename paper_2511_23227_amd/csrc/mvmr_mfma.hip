@@ -1,15 +1,23 @@
 // Matrix-core (MFMA) MVMR kernels for gfx950.
 //
-// Rows kernel (Eq. (1) forward; Sec. 3.3.3 input gradient with W^T): one wave owns 32 consecutive
-// centres and every destination channel.  For each kernel cell k it
+// Rows kernel (Eq. (1) forward; Sec. 3.3.3 input gradient with W^T): a block of four waves owns 32
+// consecutive centres and every destination channel; wave w takes the kernel cells k = w, w+4, ...
+// For each of its cells a wave
 //   1. sums the source rows of each (k, centre) run in fp32 registers -- the lanes are laid out so that
 //      the summed tile already is the MFMA A operand: lane (m = lane % 32, h = lane / 32) holds
-//      channels [h*C/2, (h+1)*C/2) of centre m -- no LDS, no barrier, waves run independently;
+//      channels [h*C/2, (h+1)*C/2) of centre m -- no LDS and no barrier on this path;
 //   2. multiplies the 32 x C_SRC tile by W[k]^T on the matrix cores into fp32 accumulators that stay
 //      in registers for the whole cell loop.
-// The reduction index of the MFMA is permuted (step s of half h <-> channel h*C/2 + s, or the s-th
-// group of 8 for bf16) identically for both operands, so every lane reads contiguous memory.
-// Each destination row is written once by its owner: no atomics, fixed summation order.
+// Run bounds and gather indices of the next cell are fetched while the rows of the current one are in
+// flight.  The reduction index of the MFMA is permuted (step s of half h <-> channel h*C/2 + s, or the
+// s-th group of 8 for bf16) identically for both operands, so every lane reads contiguous memory.
+// The four waves' accumulators are added in wave order through LDS and each destination row is
+// written once: no atomics, fixed summation order.
+//
+// Weight kernel (Eq. (5), VVOR): dW[k] = sum over the cell's run of dy[o] (x) x[i].  The triplet list
+// is cut into equal chunks, one per wave; the reduction index of the MFMA is the triplet, both
+// operands are rows read straight from memory (lane <-> channel), partial sums per chunk go to the
+// workspace and are added in a fixed order by a second kernel.
 #include "pcpp_internal.h"
 
 namespace pcpp {
@@ -24,6 +32,22 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 constexpr int WAVES = 4;
 constexpr int ROWS = 32;   // centres per wave
 
+// Per-lane predicated 16-byte load through a buffer descriptor: a lane whose offset is OOB_OFFSET is out
+// of the descriptor's range, reads zeros and causes no memory traffic, so runs of different lengths
+// need no branches around their loads.
+constexpr uint32_t OOB_OFFSET = 0xffffff00u;
+constexpr size_t MAX_BUFFER_BYTES = 0xfffff000u;
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ inline v4u buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+}
+
 __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 {
     uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
@@ -32,100 +56,90 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return (a >> 16) | (b & 0xffff0000u);
 }
 
-// ---------------------------------------------------------------------------------------------
-// fp32: v_mfma_f32_32x32x2_f32.  A: lane (m, h) gives A[m][h]; B: lane (n, h) gives B[h][n];
-// D: lane l, register j -> row 8*(j/4) + 4*(l/32) + j%4, column l%32.
-// ---------------------------------------------------------------------------------------------
-template <int C_SRC, int C_DST>
-__global__ __launch_bounds__(WAVES * 64) void rows_f32_kernel(const float *__restrict__ feat,
-                                                              const float *__restrict__ w, float *__restrict__ dst,
-                                                              int64_t n_centres, int K,
-                                                              const int32_t *__restrict__ gather, PlanSideView side)
+// MFMA register layouts used below (wave64):
+//   v_mfma_f32_32x32x2_f32 :  A: lane (m = l%32, h = l/32) gives A[m][h];  B: lane (n, h) gives B[h][n]
+//   v_mfma_f32_32x32x16_bf16: A: lane (m, h) gives A[m][8h .. 8h+7];       B: lane (n, h) gives B[8h .. 8h+7][n]
+//   D (both): lane l, register j -> row 8*(j/4) + 4*(l/32) + j%4, column l%32.
+
+// Re-lays W for the rows kernel so that each MFMA B fragment is one contiguous 1 KiB wave load:
+//   packed[((k*NB + b)*NV + v)*64 + lane] (16 bytes) = W(k, dst = b*32 + lane%32, src = (lane/32)*HALF + v*E .. +E)
+// with E = 16 / element size.  W(k, d, s) is read at w[k*c_dst*c_src + d*stride_d + s*stride_s], which
+// covers both W[k][c_out][c_in] as stored (forward) and its transpose (input gradient).
+template <typename T>
+__global__ void pack_w_kernel(const T *__restrict__ w, T *__restrict__ packed, int K, int c_src, int c_dst,
+                              int stride_d, int stride_s)
 {
-    constexpr int HALF = C_SRC / 2;       // channels per lane
-    constexpr int NV = HALF / 4;          // float4 loads per source row per lane
-    constexpr int NB = C_DST / 32;        // 32-wide destination blocks
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int m = lane & 31, h = lane >> 5;
-    const int64_t blk = (int64_t)blockIdx.x * WAVES + wave;   // 32-row block
-    const int64_t row0 = blk * ROWS;
-    if (row0 >= n_centres) return;
-    const int64_t tile = blk >> 1;
-    const int sub = (int)(blk & 1) * ROWS;                     // offset of this block inside its 64-tile
-    const bool last_in_tile = (sub + m) == TILE - 1;
-
-    v16f acc[NB];
+    constexpr int E = 16 / sizeof(T);
+    const int half = c_src / 2, nv = half / E, nb = c_dst / 32;
+    const int64_t total = (int64_t)K * nb * nv * 64;
+    const int64_t piece = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (piece >= total) return;
+    const int lane = (int)(piece & 63);
+    int64_t r = piece >> 6;
+    const int v = (int)(r % nv); r /= nv;
+    const int b = (int)(r % nb);
+    const int k = (int)(r / nb);
+    const int d = b * 32 + (lane & 31);
+    const int s0 = (lane >> 5) * half + v * E;
+    const T *src = w + (size_t)k * c_dst * c_src + (size_t)d * stride_d;
+    T *dst = packed + piece * E;
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[b][j] = 0.f;
-
-    for (int k = 0; k < K; ++k) {
-        const uint32_t *rs = side.run_start + ((size_t)tile * K + k) * TILE + sub + m;
-        const uint32_t st = rs[0];
-        const uint32_t en = last_in_tile ? side.tile_ptr[(size_t)k * side.n_tiles + tile + 1] : rs[1];
-        const uint32_t cnt = en - st;
-        if (__ballot(cnt != 0) == 0) continue;                 // no neighbour in this cell for these 32 centres
-
-        // W[k] fragments: lane (n, h) reads W[k][b*32 + n][h*HALF .. +HALF)
-        v4f bw[NB][NV];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const v4f *wp = reinterpret_cast<const v4f *>(w + ((size_t)k * C_DST + b * 32 + m) * C_SRC + h * HALF);
-#pragma unroll
-            for (int v = 0; v < NV; ++v) bw[b][v] = wp[v];
-        }
-
-        // sum of the source rows of centre m in cell k, this lane's half of the channels
-        v4f xs[NV];
-#pragma unroll
-        for (int v = 0; v < NV; ++v) xs[v] = v4f{0.f, 0.f, 0.f, 0.f};
-        for (uint32_t j = 0; j < cnt; ++j) {
-            const int32_t src = gather[st + j];
-            const v4f *xp = reinterpret_cast<const v4f *>(feat + (size_t)src * C_SRC + h * HALF);
-#pragma unroll
-            for (int v = 0; v < NV; ++v) xs[v] += xp[v];
-        }
-
-#pragma unroll
-        for (int v = 0; v < NV; ++v)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[v][e], bw[b][v][e], acc[b], 0, 0, 0);
-    }
-
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
-            if (row < n_centres) dst[(size_t)row * C_DST + b * 32 + m] = acc[b][j];
-        }
+    for (int e = 0; e < E; ++e) dst[e] = src[(size_t)(s0 + e) * stride_s];
 }
 
-// ---------------------------------------------------------------------------------------------
-// bf16: v_mfma_f32_32x32x16_bf16.  A: lane (m, h) gives A[m][8h .. 8h+7]; B likewise; D as above.
-// The summed rows are rounded to bf16 once (the inputs carry the same precision).
-// ---------------------------------------------------------------------------------------------
-template <int C_SRC, int C_DST, typename TOut>
-__global__ __launch_bounds__(WAVES * 64) void rows_bf16_kernel(const uint16_t *__restrict__ feat,
-                                                               const uint16_t *__restrict__ w,
-                                                               TOut *__restrict__ dst, int64_t n_centres, int K,
-                                                               const int32_t *__restrict__ gather, PlanSideView side)
+// KW = kernel cells per wave (compile time): the cell loop is fully unrolled so that the run bounds and
+// the first J gather indices of every cell are fetched up front, leaving one memory round trip per cell.
+template <bool BF16, int C_SRC, int C_DST, int J, int KW, typename TOut>
+__global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
+                                                          TOut *__restrict__ dst, int64_t n_centres, int K,
+                                                          const int32_t *__restrict__ gather, uint32_t last_triplet,
+                                                          uint32_t feat_bytes, PlanSideView side)
 {
-    constexpr int HALF = C_SRC / 2;       // channels per lane
-    constexpr int NV = HALF / 8;          // 16-byte loads per source row per lane = MFMA steps
-    constexpr int NB = C_DST / 32;
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr uint32_t ROWB = C_SRC * ES;    // bytes per source row
+    constexpr int HALF = C_SRC / 2;          // channels per lane
+    constexpr int NV = HALF * ES / 16;       // 16-byte loads per source row per lane
+    constexpr int NB = C_DST / 32;           // 32-wide destination blocks
+    extern __shared__ float red[];           // [WAVES - 1][NB * 16][64]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
-    const int64_t blk = (int64_t)blockIdx.x * WAVES + wave;
+    const int64_t blk = blockIdx.x;          // 32-centre block
     const int64_t row0 = blk * ROWS;
-    if (row0 >= n_centres) return;
     const int64_t tile = blk >> 1;
-    const int sub = (int)(blk & 1) * ROWS;
+    const int sub = (int)(blk & 1) * ROWS;   // offset of the block inside its 64-centre tile
     const bool last_in_tile = (sub + m) == TILE - 1;
+    const __amdgpu_buffer_rsrc_t frs = make_rsrc(feat_, feat_bytes);
+    const uint32_t lane_off = (uint32_t)h * HALF * ES;
+    // W is pre-packed in fragment order: [k][b][v][lane][16 bytes] (see pack_w_kernel)
+    const v4u *wfrag = static_cast<const v4u *>(w_) + lane;
+    const uint32_t *runs = side.run_start + (size_t)tile * K * TILE + sub + m;
+    const uint32_t *tends = side.tile_ptr + tile + 1;
+
+    // run bounds of centre m for this wave's cells, then the first J gather indices of each run
+    uint32_t st[KW], cn[KW];
+#pragma unroll
+    for (int t = 0; t < KW; ++t) {
+        const int k = wave + WAVES * t;
+        const int kc = k < K ? k : K - 1;
+        const uint32_t *pe = last_in_tile ? tends + (size_t)kc * side.n_tiles : runs + (size_t)kc * TILE + 1;
+        st[t] = runs[(size_t)kc * TILE];
+        cn[t] = *pe;
+    }
+#pragma unroll
+    for (int t = 0; t < KW; ++t) cn[t] = (wave + WAVES * t) < K ? cn[t] - st[t] : 0u;
+    int32_t idx[KW][J];
+#pragma unroll
+    for (int t = 0; t < KW; ++t)
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const uint32_t p = st[t] + j;
+            idx[t][j] = gather[p < last_triplet ? p : last_triplet];
+        }
+    // keep the index loads here, ahead of the cell loop (they would otherwise be sunk next to their uses)
+#pragma unroll
+    for (int t = 0; t < KW; ++t)
+#pragma unroll
+        for (int j = 0; j < J; ++j) asm volatile("" : "+v"(idx[t][j]));
 
     v16f acc[NB];
 #pragma unroll
@@ -133,111 +147,427 @@ __global__ __launch_bounds__(WAVES * 64) void rows_bf16_kernel(const uint16_t *_
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[b][j] = 0.f;
 
-    for (int k = 0; k < K; ++k) {
-        const uint32_t *rs = side.run_start + ((size_t)tile * K + k) * TILE + sub + m;
-        const uint32_t st = rs[0];
-        const uint32_t en = last_in_tile ? side.tile_ptr[(size_t)k * side.n_tiles + tile + 1] : rs[1];
-        const uint32_t cnt = en - st;
-        if (__ballot(cnt != 0) == 0) continue;
-
-        v4u bw[NB][NV];
+    // Two cells in flight: the loads of cell t+1 (W fragments and the first J rows of every run) are
+    // issued before the rows of cell t are consumed.  Lanes past the end of their run read through an
+    // out-of-range buffer offset (zeros, no traffic), so the issue step has no branches.
+    v4u bw[2][NB][NV];
+    v4u rv[2][J][NV];
+    auto issue = [&](int t, int buf) {
+        const int k = wave + WAVES * t;
+        const int kc = k < K ? k : K - 1;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const v4u *wp = reinterpret_cast<const v4u *>(w + ((size_t)k * C_DST + b * 32 + m) * C_SRC + h * HALF);
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int v = 0; v < NV; ++v) bw[b][v] = wp[v];
+            for (int v = 0; v < NV; ++v) bw[buf][b][v] = wfrag[(((size_t)kc * NB + b) * NV + v) * 64];
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const uint32_t off = (uint32_t)j < cn[t] ? (uint32_t)idx[t][j] * ROWB + lane_off : OOB_OFFSET;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) rv[buf][j][v] = buffer_load16(frs, off + v * 16);
         }
-
-        float xs[NV][8];
+    };
+    issue(0, 0);
 #pragma unroll
-        for (int v = 0; v < NV; ++v)
+    for (int t = 0; t < KW; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < KW) issue(t + 1, buf ^ 1);
+        const uint32_t cn_c = cn[t], st_c = st[t];
+        float xs[HALF];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) xs[v][e] = 0.f;
-        for (uint32_t j = 0; j < cnt; ++j) {
-            const int32_t src = gather[st + j];
-            const v4u *xp = reinterpret_cast<const v4u *>(feat + (size_t)src * C_SRC + h * HALF);
+        for (int c = 0; c < HALF; ++c) xs[c] = 0.f;
+        auto add_row = [&](const v4u (&r)[NV]) {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const v4u q = xp[v];
+            for (int v = 0; v < NV; ++v)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    xs[v][2 * e] += __uint_as_float(q[e] << 16);
-                    xs[v][2 * e + 1] += __uint_as_float(q[e] & 0xffff0000u);
+                    if constexpr (BF16) {
+                        xs[v * 8 + 2 * e] += __uint_as_float(r[v][e] << 16);
+                        xs[v * 8 + 2 * e + 1] += __uint_as_float(r[v][e] & 0xffff0000u);
+                    } else {
+                        xs[v * 4 + e] += __uint_as_float(r[v][e]);
+                    }
                 }
+        };
+#pragma unroll
+        for (int j = 0; j < J; ++j) add_row(rv[buf][j]);
+        // runs longer than J
+        for (uint32_t j0 = J; j0 < cn_c; j0 += J) {
+            int32_t ix[J];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const uint32_t p = st_c + j0 + j;
+                ix[j] = gather[p < last_triplet ? p : last_triplet];
             }
+            v4u rr[J][NV];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const uint32_t off = j0 + j < cn_c ? (uint32_t)ix[j] * ROWB + lane_off : OOB_OFFSET;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) rr[j][v] = buffer_load16(frs, off + v * 16);
+            }
+#pragma unroll
+            for (int j = 0; j < J; ++j) add_row(rr[j]);
         }
-
+        if constexpr (BF16) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            v4u a;
+            for (int v = 0; v < NV; ++v) {
+                v4u a;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) a[e] = pack_bf16x2(xs[v][2 * e], xs[v][2 * e + 1]);
-            const v8bf av = __builtin_bit_cast(v8bf, a);
+                for (int e = 0; e < 4; ++e) a[e] = pack_bf16x2(xs[v * 8 + 2 * e], xs[v * 8 + 2 * e + 1]);
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(v8bf, bw[b][v]), acc[b], 0, 0, 0);
+                for (int b = 0; b < NB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a),
+                                                                     __builtin_bit_cast(v8bf, bw[buf][b][v]), acc[b], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[v * 4 + e], __uint_as_float(bw[buf][b][v][e]),
+                                                                      acc[b], 0, 0, 0);
         }
     }
 
+    // add the four waves' accumulators in wave order, wave 0 writes the rows
+    if (wave > 0) {
+        float *mine = red + (size_t)(wave - 1) * NB * 16 * 64;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mine[(b * 16 + j) * 64 + lane] = acc[b][j];
+    }
+    __syncthreads();
+    if (wave != 0) return;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
+            float v = acc[b][j];
+#pragma unroll
+            for (int wv = 0; wv < WAVES - 1; ++wv) v += red[((size_t)wv * NB * 16 + b * 16 + j) * 64 + lane];
             const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
             if (row < n_centres) {
-                if constexpr (sizeof(TOut) == 4) {
-                    dst[(size_t)row * C_DST + b * 32 + m] = acc[b][j];
-                } else {
-                    dst[(size_t)row * C_DST + b * 32 + m] = (uint16_t)(pack_bf16x2(acc[b][j], 0.f) & 0xffffu);
-                }
+                if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + b * 32 + m] = v;
+                else dst[(size_t)row * C_DST + b * 32 + m] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
             }
         }
 }
 
-template <int C_SRC, int C_DST>
-int launch_f32(const MvmrArgs &a, hipStream_t stream)
+// ---------------------------------------------------------------------------------------------
+// Weight gradient (VVOR), Eq. (5).  Wave c owns triplets [c*chunk, (c+1)*chunk) of the (k, o, i)
+// ordered list.  A chunk usually lies inside one cell's run; where a run starts inside the chunk the
+// accumulator is flushed and restarted.  Slots of the partial buffer:
+//   slot c               sum for the cell of the chunk's first triplet
+//   slot n_chunks + k    sum for cell k over the part of its run that starts inside a chunk
+// fp32: one MFMA step consumes 2 triplets: lane (c, h) supplies channel c of dy[o] and of x[i] of
+// triplet 2 s + h.  bf16: one step consumes 16 triplets; a lane reads one dword (2 channels) per
+// triplet and the even / odd channels form separate 32-wide blocks of the operand.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16, int C_IN, int C_OUT>
+__global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
+                                                            float *__restrict__ part,
+                                                            const int32_t *__restrict__ tri_o,
+                                                            const int32_t *__restrict__ tri_i,
+                                                            const int64_t *__restrict__ seg, int K, int64_t n_triplets,
+                                                            int chunk, int64_t n_chunks)
 {
-    const int64_t blocks = ceil_div(ceil_div(a.n_centres, ROWS), WAVES);
-    rows_f32_kernel<C_SRC, C_DST><<<(unsigned)blocks, WAVES * 64, 0, stream>>>(
-        static_cast<const float *>(a.feat), static_cast<const float *>(a.w), static_cast<float *>(a.dst),
-        a.n_centres, a.K, a.gather, a.side);
+    constexpr int NBI = C_IN / 32, NBO = C_OUT / 32;
+    constexpr int STEP = BF16 ? 16 : 2;      // triplets per MFMA step
+    constexpr int NS = 32 / STEP;            // steps per batch of 32 triplets
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int64_t chunk_id = (int64_t)blockIdx.x * WAVES + wave;
+    if (chunk_id >= n_chunks) return;
+    int64_t p = chunk_id * chunk;
+    int64_t p_end = p + chunk;
+    if (p_end > n_triplets) p_end = n_triplets;
+
+    // cell of the first triplet: the k with seg[k] <= p < seg[k+1]
+    int k = 0;
+    for (int kb = 0; kb < K; kb += 64) {
+        const int kk = kb + lane;
+        const bool hit = kk < K && seg[kk] <= p && p < seg[kk + 1];
+        const unsigned long long msk = __ballot(hit);
+        if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
+    }
+
+    v16f acc[NBO][NBI];
+    bool first = true;
+    while (p < p_end) {
+        int64_t q = seg[k + 1];
+        if (q > p_end) q = p_end;
+        if (q <= p) { ++k; continue; }       // empty run
+#pragma unroll
+        for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+            for (int bi = 0; bi < NBI; ++bi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[bo][bi][j] = 0.f;
+
+        for (int64_t b0 = p; b0 < q; b0 += 32) {
+            const int n = (int)(q - b0 < 32 ? q - b0 : 32);
+            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
+            int32_t oi = 0;
+            if (c < n) oi = h == 0 ? tri_o[b0 + c] : tri_i[b0 + c];
+            if constexpr (!BF16) {
+                float a[NBO][NS], b[NBI][NS];
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const int t = 2 * s + h;
+                    const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
+                    const float *dyr = static_cast<const float *>(dy_) + (size_t)o * C_OUT + c;
+                    const float *xr = static_cast<const float *>(x_) + (size_t)i * C_IN + c;
+#pragma unroll
+                    for (int bo = 0; bo < NBO; ++bo) a[bo][s] = t < n ? dyr[bo * 32] : 0.f;
+#pragma unroll
+                    for (int bi = 0; bi < NBI; ++bi) b[bi][s] = t < n ? xr[bi * 32] : 0.f;
+                }
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+                        for (int bi = 0; bi < NBI; ++bi)
+                            acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bo][s], b[bi][s], acc[bo][bi], 0, 0, 0);
+            } else {
+                // block index of the operand = 2 * q + parity: channel 2 * (c + 32 q) + parity
+                constexpr int QO = C_OUT / 64, QI = C_IN / 64;
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    uint32_t dyw[QO][8], xw[QI][8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int t = 16 * s + 8 * h + e;
+                        const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
+                        const uint32_t *dyr = static_cast<const uint32_t *>(dy_) + (size_t)o * (C_OUT / 2) + c;
+                        const uint32_t *xr = static_cast<const uint32_t *>(x_) + (size_t)i * (C_IN / 2) + c;
+#pragma unroll
+                        for (int qo = 0; qo < QO; ++qo) dyw[qo][e] = t < n ? dyr[qo * 32] : 0u;
+#pragma unroll
+                        for (int qi = 0; qi < QI; ++qi) xw[qi][e] = t < n ? xr[qi * 32] : 0u;
+                    }
+                    v4u av[NBO], bv[NBI];
+#pragma unroll
+                    for (int qo = 0; qo < QO; ++qo)
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; ++e2) {
+                            av[2 * qo][e2] = (dyw[qo][2 * e2] & 0xffffu) | (dyw[qo][2 * e2 + 1] << 16);
+                            av[2 * qo + 1][e2] = (dyw[qo][2 * e2] >> 16) | (dyw[qo][2 * e2 + 1] & 0xffff0000u);
+                        }
+#pragma unroll
+                    for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; ++e2) {
+                            bv[2 * qi][e2] = (xw[qi][2 * e2] & 0xffffu) | (xw[qi][2 * e2 + 1] << 16);
+                            bv[2 * qi + 1][e2] = (xw[qi][2 * e2] >> 16) | (xw[qi][2 * e2 + 1] & 0xffff0000u);
+                        }
+#pragma unroll
+                    for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+                        for (int bi = 0; bi < NBI; ++bi)
+                            acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av[bo]),
+                                                                                  __builtin_bit_cast(v8bf, bv[bi]),
+                                                                                  acc[bo][bi], 0, 0, 0);
+                }
+            }
+        }
+        // flush
+        float *dstp = part + (size_t)(first ? chunk_id : n_chunks + k) * C_OUT * C_IN;
+#pragma unroll
+        for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+            for (int bi = 0; bi < NBI; ++bi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int r = 8 * (j / 4) + 4 * h + (j % 4);
+                    int co, ci;
+                    if constexpr (BF16) {
+                        co = 2 * (r + 32 * (bo >> 1)) + (bo & 1);
+                        ci = 2 * (c + 32 * (bi >> 1)) + (bi & 1);
+                    } else {
+                        co = bo * 32 + r;
+                        ci = bi * 32 + c;
+                    }
+                    dstp[(size_t)co * C_IN + ci] = acc[bo][bi][j];
+                }
+        first = false;
+        p = q;
+        ++k;
+    }
+}
+
+// dw[k][e] = (partial of the run's head, if it starts inside a chunk) + partials of the chunks whose first
+// triplet lies in run k.  16 threads share one element: thread g adds chunks c0+g, c0+g+16, ... in
+// ascending order and the 16 sums are then added in order of g, so the result is reproducible.
+// grid = (ceil(c_out*c_in / 16), K), block = 256
+__global__ __launch_bounds__(256) void weight_reduce(const float *__restrict__ part, float *__restrict__ dw,
+                                                     const int64_t *__restrict__ seg, int n_elem, int chunk,
+                                                     int64_t n_chunks)
+{
+    __shared__ float sums[16][17];
+    const int el = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const int e = blockIdx.x * 16 + el;
+    const int k = blockIdx.y;
+    const int64_t s = seg[k], t = seg[k + 1];
+    float v = 0.f;
+    if (t > s && e < n_elem) {
+        const int64_t c0 = (s + chunk - 1) / chunk, c1 = (t + chunk - 1) / chunk;
+        for (int64_t c = c0 + g; c < c1; c += 16) v += part[(size_t)c * n_elem + e];
+    }
+    sums[g][el] = v;
+    __syncthreads();
+    if (g == 0 && e < n_elem) {
+        float r = (t > s && s % chunk != 0) ? part[(size_t)(n_chunks + k) * n_elem + e] : 0.f;
+#pragma unroll
+        for (int gg = 0; gg < 16; ++gg) r += sums[gg][el];
+        dw[(size_t)k * n_elem + e] = r;
+    }
+}
+
+// triplets per wave: at least 512, grown so that there are at most about 8192 chunks
+int weight_chunk(int64_t n_triplets)
+{
+    int chunk = 512;
+    while ((n_triplets + chunk - 1) / chunk > 8192) chunk *= 2;
+    return chunk;
+}
+
+template <bool BF16, int C_IN, int C_OUT>
+int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int64_t *seg, void *workspace,
+                  size_t workspace_bytes, hipStream_t stream)
+{
+    const int n_elem = C_IN * C_OUT;
+    const int chunk = weight_chunk(a.n_triplets);
+    const int64_t n_chunks = ceil_div(a.n_triplets, chunk);
+    const size_t need = (size_t)(n_chunks + a.K) * n_elem * sizeof(float);
+    if (workspace_bytes < need) {
+        set_error("pcpp_mvmr_bwd_weight: workspace has %zu bytes, needs %zu", workspace_bytes, need);
+        return PCPP_ERR_WORKSPACE;
+    }
+    float *part = static_cast<float *>(workspace);
+    if (n_chunks > 0) {
+        weight_kernel<BF16, C_IN, C_OUT><<<(unsigned)ceil_div(n_chunks, WAVES), WAVES * 64, 0, stream>>>(
+            a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
+    dim3 grid((unsigned)ceil_div(n_elem, 16), (unsigned)a.K);
+    weight_reduce<<<grid, 256, 0, stream>>>(part, dw, seg, n_elem, chunk, n_chunks);
     PCPP_HIP_CHECK(hipGetLastError());
     return PCPP_OK;
 }
 
-template <int C_SRC, int C_DST>
-int launch_bf16(const MvmrArgs &a, hipStream_t stream)
+bool weight_shape_supported(int in_dtype, int c_in, int c_out)
 {
-    const int64_t blocks = ceil_div(ceil_div(a.n_centres, ROWS), WAVES);
-    if (a.out_dtype == PCPP_F32)
-        rows_bf16_kernel<C_SRC, C_DST, float><<<(unsigned)blocks, WAVES * 64, 0, stream>>>(
-            static_cast<const uint16_t *>(a.feat), static_cast<const uint16_t *>(a.w), static_cast<float *>(a.dst),
-            a.n_centres, a.K, a.gather, a.side);
-    else
-        rows_bf16_kernel<C_SRC, C_DST, uint16_t><<<(unsigned)blocks, WAVES * 64, 0, stream>>>(
-            static_cast<const uint16_t *>(a.feat), static_cast<const uint16_t *>(a.w),
-            static_cast<uint16_t *>(a.dst), a.n_centres, a.K, a.gather, a.side);
+    if (in_dtype == PCPP_F32) return (c_in == 32 && c_out == 32) || (c_in == 64 && c_out == 64);
+    return (c_in == 64 && c_out == 64) || (c_in == 64 && c_out == 128) || (c_in == 128 && c_out == 128);
+}
+
+template <bool BF16, int C_SRC, int C_DST, int J, int KW>
+int launch_rows_kw(const MvmrArgs &a, hipStream_t stream)
+{
+    const int64_t blocks = ceil_div(a.n_centres, ROWS);
+    const size_t lds = (size_t)(WAVES - 1) * (C_DST / 32) * 16 * 64 * sizeof(float);
+    const uint32_t last = (uint32_t)(a.n_triplets - 1);
+    const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * (BF16 ? 2 : 4));
+    if (a.out_dtype == PCPP_F32) {
+        rows_kernel<BF16, C_SRC, C_DST, J, KW, float><<<(unsigned)blocks, WAVES * 64, lds, stream>>>(
+            a.feat, a.w, static_cast<float *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+    } else {
+        rows_kernel<BF16, C_SRC, C_DST, J, KW, uint16_t><<<(unsigned)blocks, WAVES * 64, lds, stream>>>(
+            a.feat, a.w, static_cast<uint16_t *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+    }
     PCPP_HIP_CHECK(hipGetLastError());
+    return PCPP_OK;
+}
+
+// cells per wave: 7 covers K <= 28 (t <= 3); larger kernels fall back to the generic path
+template <bool BF16, int C_SRC, int C_DST, int J>
+int launch_rows(const MvmrArgs &a, hipStream_t stream, bool *handled)
+{
+    if ((size_t)a.n_src * C_SRC * (BF16 ? 2 : 4) > MAX_BUFFER_BYTES) { *handled = false; return PCPP_OK; }
+    if (a.K <= 4 * 2) return launch_rows_kw<BF16, C_SRC, C_DST, J, 2>(a, stream);
+    if (a.K <= 4 * 7) return launch_rows_kw<BF16, C_SRC, C_DST, J, 7>(a, stream);
+    *handled = false;
     return PCPP_OK;
 }
 
 }  // namespace
 
+bool mvmr_rows_mfma_supported(const MvmrArgs &a)
+{
+    if (a.n_triplets <= 0 || a.K > 28) return false;
+    const size_t es = a.in_dtype == PCPP_BF16 ? 2 : 4;
+    if ((size_t)a.n_src * a.c_src * es > MAX_BUFFER_BYTES) return false;
+    if (a.in_dtype == PCPP_F32 && a.out_dtype == PCPP_F32)
+        return (a.c_src == 32 && a.c_dst == 32) || (a.c_src == 16 && a.c_dst == 32) || (a.c_src == 64 && a.c_dst == 64);
+    if (a.in_dtype == PCPP_BF16)
+        return (a.c_src == 64 && a.c_dst == 64) || (a.c_src == 64 && a.c_dst == 128) ||
+               (a.c_src == 128 && a.c_dst == 64) || (a.c_src == 32 && a.c_dst == 32);
+    return false;
+}
+
+// Packs W(k, d, s) = w[k*c_dst*c_src + d*stride_d + s*stride_s] into `packed` (K*c_dst*c_src elements).
+int mvmr_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s, int dtype,
+                hipStream_t stream)
+{
+    const int e = dtype == PCPP_BF16 ? 8 : 4;
+    const int64_t total = (int64_t)K * (c_dst / 32) * (c_src / 2 / e) * 64;
+    const unsigned blocks = (unsigned)ceil_div(total, 256);
+    if (dtype == PCPP_BF16)
+        pack_w_kernel<uint16_t><<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w),
+                                                            static_cast<uint16_t *>(packed), K, c_src, c_dst,
+                                                            stride_d, stride_s);
+    else
+        pack_w_kernel<float><<<blocks, 256, 0, stream>>>(static_cast<const float *>(w), static_cast<float *>(packed),
+                                                         K, c_src, c_dst, stride_d, stride_s);
+    PCPP_HIP_CHECK(hipGetLastError());
+    return PCPP_OK;
+}
+
+// a.w must be the packed weights
 int mvmr_rows_mfma(const MvmrArgs &a, hipStream_t stream, bool *handled)
 {
     *handled = true;
-    if (a.in_dtype == PCPP_F32) {
-        if (a.c_src == 32 && a.c_dst == 32) return launch_f32<32, 32>(a, stream);
-        if (a.c_src == 16 && a.c_dst == 32) return launch_f32<16, 32>(a, stream);
-        if (a.c_src == 64 && a.c_dst == 64) return launch_f32<64, 64>(a, stream);
-    } else {
-        if (a.c_src == 64 && a.c_dst == 64) return launch_bf16<64, 64>(a, stream);
-        if (a.c_src == 64 && a.c_dst == 128) return launch_bf16<64, 128>(a, stream);
-        if (a.c_src == 128 && a.c_dst == 64) return launch_bf16<128, 64>(a, stream);
-        if (a.c_src == 32 && a.c_dst == 32) return launch_bf16<32, 32>(a, stream);
+    if (!mvmr_rows_mfma_supported(a)) { *handled = false; return PCPP_OK; }
+    if (a.in_dtype == PCPP_F32 && a.out_dtype == PCPP_F32) {
+        if (a.c_src == 32 && a.c_dst == 32) return launch_rows<false, 32, 32, 2>(a, stream, handled);
+        if (a.c_src == 16 && a.c_dst == 32) return launch_rows<false, 16, 32, 2>(a, stream, handled);
+        if (a.c_src == 64 && a.c_dst == 64) return launch_rows<false, 64, 64, 2>(a, stream, handled);
+    } else if (a.in_dtype == PCPP_BF16) {
+        if (a.c_src == 64 && a.c_dst == 64) return launch_rows<true, 64, 64, 2>(a, stream, handled);
+        if (a.c_src == 64 && a.c_dst == 128) return launch_rows<true, 64, 128, 2>(a, stream, handled);
+        if (a.c_src == 128 && a.c_dst == 64) return launch_rows<true, 128, 64, 1>(a, stream, handled);
+        if (a.c_src == 32 && a.c_dst == 32) return launch_rows<true, 32, 32, 2>(a, stream, handled);
     }
     *handled = false;
     return PCPP_OK;
+}
+
+// c_src = c_in (x), c_dst = c_out (dy, passed as `dense`); gather = tri_i
+int mvmr_weight_mfma(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int64_t *seg, void *workspace,
+                     size_t workspace_bytes, hipStream_t stream, bool *handled)
+{
+    *handled = true;
+    if (a.in_dtype == PCPP_F32) {
+        if (a.c_src == 32 && a.c_dst == 32) return launch_weight<false, 32, 32>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 64 && a.c_dst == 64) return launch_weight<false, 64, 64>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+    } else {
+        if (a.c_src == 64 && a.c_dst == 64) return launch_weight<true, 64, 64>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 64 && a.c_dst == 128) return launch_weight<true, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 128 && a.c_dst == 128) return launch_weight<true, 128, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+    }
+    *handled = false;
+    return PCPP_OK;
+}
+
+size_t mvmr_weight_mfma_workspace_bytes(int64_t n_triplets, int c_in, int c_out, int K, int in_dtype)
+{
+    if (!weight_shape_supported(in_dtype, c_in, c_out)) return 0;
+    const int chunk = weight_chunk(n_triplets);
+    return align_up((size_t)(ceil_div(n_triplets, chunk) + K) * c_in * c_out * sizeof(float));
 }
 
 }  // namespace pcpp

@@ -96,13 +96,18 @@ const char *pcpp_last_error(void) { return g_error; }
 
 int pcpp_version(void) { return 100; }
 
-size_t pcpp_mvmr_workspace_bytes(int op, int64_t n_in, int64_t n_out, int c_in, int c_out, int K, int in_dtype)
+size_t pcpp_mvmr_workspace_bytes(int op, int64_t n_in, int64_t n_out, int64_t n_triplets, int c_in, int c_out, int K,
+                                 int in_dtype)
 {
-    if (n_in < 0 || n_out < 0 || c_in < 1 || c_out < 1 || K < 1) return 0;
+    if (n_in < 0 || n_out < 0 || n_triplets < 0 || c_in < 1 || c_out < 1 || K < 1) return 0;
     switch (op) {
-    case 0: return 256;
-    case 1: return align_up((size_t)K * c_out * c_in * elem_size(in_dtype));   // W^T
-    case 2: return mvmr_weight_workspace_bytes(n_out, c_in, c_out, K);          // partial dW per tile range
+    case 0:                                                                     // W in fragment order
+    case 1: return align_up((size_t)K * c_out * c_in * elem_size(in_dtype));   // W^T, plain or in fragment order
+    case 2: {                                                                   // partial dW per range of centres
+        const size_t g = mvmr_weight_workspace_bytes(n_out, c_in, c_out, K);
+        const size_t m = mvmr_weight_mfma_workspace_bytes(n_triplets, c_in, c_out, K, in_dtype);
+        return g > m ? g : m;
+    }
     default: return 0;
     }
 }
@@ -112,7 +117,6 @@ int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out
                   const int32_t *tri_k, const int64_t *seg_offsets, int64_t n_triplets, const void *plan,
                   void *workspace, size_t workspace_bytes, void *stream_)
 {
-    (void)workspace; (void)workspace_bytes;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     int rc = check_common("pcpp_mvmr_fwd", x, w, out, in_dtype, out_dtype, n_in, n_out, c_in, c_out, K, tri_o, tri_i,
                           tri_k, seg_offsets, n_triplets, plan);
@@ -127,9 +131,17 @@ int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out
     a.in_dtype = in_dtype; a.out_dtype = out_dtype;
     a.n_src = n_in; a.n_centres = n_out; a.c_src = c_in; a.c_dst = c_out; a.K = K;
     a.gather = tri_i; a.side = side_view(plan, pl.fwd); a.n_triplets = n_triplets;
-    bool handled = false;
-    rc = mvmr_rows_mfma(a, stream, &handled);
-    if (rc != PCPP_OK || handled) return rc;
+    if (mvmr_rows_mfma_supported(a)) {
+        const size_t need = pcpp_mvmr_workspace_bytes(0, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
+        if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
+            set_error("pcpp_mvmr_fwd: workspace missing, misaligned or smaller than %zu bytes", need);
+            return PCPP_ERR_WORKSPACE;
+        }
+        if ((rc = mvmr_pack_w(w, workspace, K, c_in, c_out, c_in, 1, in_dtype, stream)) != PCPP_OK) return rc;
+        a.w = workspace;
+        bool handled = false;
+        return mvmr_rows_mfma(a, stream, &handled);
+    }
     return mvmr_rows_generic(a, stream);
 }
 
@@ -144,23 +156,25 @@ int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, i
     if (rc != PCPP_OK) return rc;
     const int t = cube_root(K);
     if (t < 0) { set_error("pcpp_mvmr_bwd_input: K must be a cube"); return PCPP_ERR_INVALID_ARG; }
-    const size_t need = pcpp_mvmr_workspace_bytes(1, n_in, n_out, c_in, c_out, K, in_dtype);
+    const size_t need = pcpp_mvmr_workspace_bytes(1, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
         set_error("pcpp_mvmr_bwd_input: workspace missing, misaligned or smaller than %zu bytes", need);
         return PCPP_ERR_WORKSPACE;
     }
     if (n_in == 0) return PCPP_OK;
-    // W[k] is [c_out][c_in]; the rows kernel wants [c_dst][c_src] = W[k]^T, so transpose once
-    if ((rc = transpose_w(w, workspace, K, c_out, c_in, in_dtype, stream)) != PCPP_OK) return rc;
     const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT);
     MvmrArgs a{};
     a.feat = dy; a.w = workspace; a.dst = dx; a.dense = nullptr;
     a.in_dtype = in_dtype; a.out_dtype = out_dtype;
     a.n_src = n_out; a.n_centres = n_in; a.c_src = c_out; a.c_dst = c_in; a.K = K;
     a.side = side_view(plan, pl.bwd); a.gather = a.side.gather; a.n_triplets = n_triplets;
-    bool handled = false;
-    rc = mvmr_rows_mfma(a, stream, &handled);
-    if (rc != PCPP_OK || handled) return rc;
+    // W[k] is [c_out][c_in]; the rows kernel wants (dst = c_in, src = c_out) = W[k]^T
+    if (mvmr_rows_mfma_supported(a)) {
+        if ((rc = mvmr_pack_w(w, workspace, K, c_out, c_in, 1, c_in, in_dtype, stream)) != PCPP_OK) return rc;
+        bool handled = false;
+        return mvmr_rows_mfma(a, stream, &handled);
+    }
+    if ((rc = transpose_w(w, workspace, K, c_out, c_in, in_dtype, stream)) != PCPP_OK) return rc;
     return mvmr_rows_generic(a, stream);
 }
 
@@ -175,7 +189,7 @@ int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype,
     if (rc != PCPP_OK) return rc;
     const int t = cube_root(K);
     if (t < 0) { set_error("pcpp_mvmr_bwd_weight: K must be a cube"); return PCPP_ERR_INVALID_ARG; }
-    const size_t need = pcpp_mvmr_workspace_bytes(2, n_in, n_out, c_in, c_out, K, in_dtype);
+    const size_t need = pcpp_mvmr_workspace_bytes(2, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
         set_error("pcpp_mvmr_bwd_weight: workspace missing, misaligned or smaller than %zu bytes", need);
         return PCPP_ERR_WORKSPACE;
@@ -186,6 +200,10 @@ int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype,
     a.in_dtype = in_dtype; a.out_dtype = PCPP_F32;
     a.n_src = n_in; a.n_centres = n_out; a.c_src = c_in; a.c_dst = c_out; a.K = K;
     a.gather = tri_i; a.side = side_view(plan, pl.fwd); a.n_triplets = n_triplets;
+    bool handled = false;
+    if (n_triplets == 0) return fill_u32(reinterpret_cast<uint32_t *>(dw), 0u, (int64_t)K * c_out * c_in, stream);
+    rc = mvmr_weight_mfma(a, dw, tri_o, seg_offsets, workspace, workspace_bytes, stream, &handled);
+    if (rc != PCPP_OK || handled) return rc;
     return mvmr_weight_generic(a, dw, workspace, workspace_bytes, stream);
 }
 

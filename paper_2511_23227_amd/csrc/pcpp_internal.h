@@ -88,10 +88,16 @@ struct MvmrArgs {
 };
 
 int mvmr_rows_generic(const MvmrArgs &a, hipStream_t stream);              // fwd and bwd_input
-int mvmr_rows_mfma(const MvmrArgs &a, hipStream_t stream, bool *handled);  // tuned shapes
+bool mvmr_rows_mfma_supported(const MvmrArgs &a);
+int mvmr_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s, int dtype,
+                hipStream_t stream);
+int mvmr_rows_mfma(const MvmrArgs &a, hipStream_t stream, bool *handled);  // tuned shapes; a.w = packed weights
 int transpose_w(const void *w, void *wt, int K, int c_out, int c_in, int dtype, hipStream_t stream);
 int mvmr_weight_generic(const MvmrArgs &a, float *dw, void *workspace, size_t workspace_bytes,
                         hipStream_t stream);
 size_t mvmr_weight_workspace_bytes(int64_t n_centres, int c_in, int c_out, int K);
+int mvmr_weight_mfma(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int64_t *seg_offsets, void *workspace,
+                     size_t workspace_bytes, hipStream_t stream, bool *handled);
+size_t mvmr_weight_mfma_workspace_bytes(int64_t n_triplets, int c_in, int c_out, int K, int in_dtype);
 
 }  // namespace pcpp

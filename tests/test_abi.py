@@ -28,7 +28,7 @@ def test_size_queries_and_argument_errors_without_gpu():
     a = L.pcpp_plan_bytes(1000, 500, 3, 20000, 1)
     b = L.pcpp_plan_bytes(1000, 500, 3, 20000, 3)
     assert 0 < a < b and a % 256 == 0 and b % 256 == 0
-    assert L.pcpp_mvmr_workspace_bytes(1, 10, 10, 8, 4, 27, 1) >= 27 * 8 * 4 * 2
+    assert L.pcpp_mvmr_workspace_bytes(1, 10, 10, 50, 8, 4, 27, 1) >= 27 * 8 * 4 * 2
     # argument validation happens before any GPU call
     n = ctypes.c_int64(-7)
     rc = L.pcpp_build_triplets(None, 5, None, 5, 0.1, 3, None, None, None, 0, None, ctypes.byref(n), None, 0, 0,
