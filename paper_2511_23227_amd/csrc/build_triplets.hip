@@ -19,7 +19,7 @@ constexpr int CELL_BIAS = 1 << 20;
 constexpr double CELL_CLAMP = (double)((1 << 20) - 2);   // +-1 stencil steps stay inside 21 bits
 constexpr int SEARCH_THREADS = 256;
 constexpr int SEARCH_WAVES = SEARCH_THREADS / 64;
-constexpr int LIST_CAP_MAX = 1024;                        // neighbours of one centre kept in LDS
+constexpr int LIST_CAP_MAX = 2048;                        // neighbours of one centre kept in LDS
 
 __device__ inline uint32_t hash_key(unsigned long long k)
 {
@@ -218,8 +218,16 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__res
 }
 
 // ---- pass 2: write every triplet to its place in (k, centre, other) order ----------------------
-//   tile_ptr  [K * n_tiles + 1]  exclusive prefix sum of tile_k_cnt
+//   tile_cnt  [n_tiles][K][TILE]  counts from pass 1
+//   tile_ptr  [K * n_tiles + 1]   exclusive prefix sum of tile_k_cnt
 //   out_c / out_b / out_k: centre index, candidate index, cell of each triplet (any may be NULL)
+// One wave per centre at a time.  The centre's neighbours are compacted into per-cell buckets of an
+// LDS list with wave ballots and prefix popcounts (the bucket sizes are the counts of pass 1), then
+// each neighbour's rank inside its bucket (number of smaller candidate indices) gives its final slot,
+// so ties between equal (k, centre) are ordered by the other index without any global sort.
+constexpr int KGROUPS = (MAX_K + 63) / 64;
+constexpr uint32_t SMALL_LIST = 160;      // up to this many neighbours the all-pairs rank is cheaper than bucketing
+
 template <bool SWAP>
 __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__restrict__ centres, int64_t n_centres,
                                                              GridView g, QueryParams q, int K, int64_t n_tiles,
@@ -230,13 +238,11 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
                                                              uint32_t *__restrict__ run_start_out, int list_cap)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
-    __shared__ unsigned long long list_all[SEARCH_WAVES][LIST_CAP_MAX];
+    __shared__ uint32_t list_all[SEARCH_WAVES][LIST_CAP_MAX];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
-    {
-        const uint32_t *src = tile_cnt + (size_t)tile * K * TILE;
-        for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = src[idx];
-    }
+    const uint32_t *cnt_tile = tile_cnt + (size_t)tile * K * TILE;
+    for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = cnt_tile[idx];
     __syncthreads();
     for (int k = wave; k < K; k += SEARCH_WAVES) {
         const uint32_t v = tbl[k * TILE + lane];
@@ -248,37 +254,112 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
         uint32_t *dst = run_start_out + (size_t)tile * K * TILE;
         for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) dst[idx] = tbl[idx];
     }
-    volatile unsigned long long *list = list_all[wave];
+    uint32_t *list = list_all[wave];
     const unsigned long long lane_lt = (1ull << lane) - 1ull;
     for (int al = wave; al < TILE; al += SEARCH_WAVES) {
         const int64_t a = tile * TILE + al;
         if (a >= n_centres) break;             // wave-uniform
+        // bucket of cell k = [bbase, bbase + bcnt) in the list; lane (k % 64) of group (k / 64) holds it
+        uint32_t bcnt[KGROUPS], bbase[KGROUPS], bcur[KGROUPS];
+        uint32_t n = 0;
+#pragma unroll
+        for (int gi = 0; gi < KGROUPS; ++gi) {
+            bcnt[gi] = 0; bbase[gi] = n; bcur[gi] = 0;
+            if (gi * 64 < K) {                 // wave-uniform
+                const int k = gi * 64 + lane;
+                bcnt[gi] = k < K ? cnt_tile[k * TILE + al] : 0u;
+                const uint32_t inc = wave_incl_scan_u32(bcnt[gi], lane);
+                bbase[gi] = n + inc - bcnt[gi];
+                n += __shfl(inc, 63, 64);
+            }
+        }
+        if (n == 0) continue;                  // wave-uniform
         Candidates<SWAP> c;
         c.open(centres, a, g, lane);
-        // neighbours of this centre, compacted into the wave's list by ballot + prefix popcount
-        uint32_t n = 0;
-        for (uint32_t base = 0; base < c.total; base += 64) {
-            int b, k;
-            const bool hit = c.fetch(base + lane, g, q, b, k);
-            const unsigned long long m = __ballot(hit);
-            const uint32_t pos = n + (uint32_t)__popcll(m & lane_lt);
-            if (hit && pos < (uint32_t)list_cap) list[pos] = ((unsigned long long)(uint32_t)k << 32) | (uint32_t)b;
-            n += (uint32_t)__popcll(m);
-        }
-        __builtin_amdgcn_wave_barrier();
-        if (n <= (uint32_t)list_cap) {
-            // rank of each neighbour among those with the same cell and a smaller index
+        if (n <= SMALL_LIST && n <= (uint32_t)list_cap) {
+            // few neighbours: one flat list of (cell, index) keys in arrival order, rank by comparing all pairs
+            unsigned long long *keys = reinterpret_cast<unsigned long long *>(list);
+            uint32_t filled = 0;
+            for (uint32_t base = 0; base < c.total; base += 64) {
+                int b, k;
+                const bool hit = c.fetch(base + lane, g, q, b, k);
+                const unsigned long long m = __ballot(hit);
+                if (hit) keys[filled + (uint32_t)__popcll(m & lane_lt)] = ((unsigned long long)(uint32_t)k << 32) | (uint32_t)b;
+                filled += (uint32_t)__popcll(m);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
             for (uint32_t e = lane; e < n; e += 64) {
-                const unsigned long long key = list[e];
+                const unsigned long long key = keys[e];
                 const unsigned long long kbase = key & 0xffffffff00000000ull;
                 const unsigned long long rel = key - kbase;
-                uint32_t rank = 0;
-                for (uint32_t e2 = 0; e2 < n; ++e2) rank += ((list[e2] - kbase) < rel) ? 1u : 0u;
+                uint32_t rank = 0, e2 = 0;
+                for (; e2 + 8 <= n; e2 += 8) {
+                    unsigned long long v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = keys[e2 + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) rank += ((v[u] - kbase) < rel) ? 1u : 0u;
+                }
+                for (; e2 < n; ++e2) rank += ((keys[e2] - kbase) < rel) ? 1u : 0u;
                 const int k = (int)(key >> 32);
                 const uint32_t pos = tbl[k * TILE + al] + rank;
                 if (out_c) out_c[pos] = (int32_t)a;
                 if (out_b) out_b[pos] = (int32_t)(uint32_t)key;
                 if (out_k) out_k[pos] = k;
+            }
+        } else if (n <= (uint32_t)list_cap) {
+            for (uint32_t base = 0; base < c.total; base += 64) {
+                int b, k;
+                const bool hit = c.fetch(base + lane, g, q, b, k);
+                unsigned long long rem = __ballot(hit);
+                while (rem) {                  // one round per distinct cell among this batch's hits
+                    const int kk = __shfl(k, __ffsll((long long)rem) - 1, 64);
+                    const unsigned long long mk = __ballot(hit && k == kk);
+                    uint32_t slot0 = 0;
+#pragma unroll
+                    for (int gi = 0; gi < KGROUPS; ++gi)
+                        if ((kk >> 6) == gi) {
+                            slot0 = __shfl(bbase[gi] + bcur[gi], kk & 63, 64);
+                            if (lane == (kk & 63)) bcur[gi] += (uint32_t)__popcll(mk);
+                        }
+                    if (hit && k == kk) list[slot0 + (uint32_t)__popcll(mk & lane_lt)] = (uint32_t)b;
+                    rem &= ~mk;
+                }
+            }
+            // the list was written by other lanes of this wave: LDS operations of one wave complete in
+            // order, the fence keeps the compiler from moving the reads above the writes
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int gi = 0; gi < KGROUPS; ++gi) {
+                unsigned long long occ = __ballot(bcnt[gi] != 0);
+                while (occ) {                  // buckets of this group, ascending cell
+                    const int kl = __ffsll((long long)occ) - 1;
+                    occ &= occ - 1;
+                    const int k = gi * 64 + kl;
+                    const uint32_t nk = __shfl(bcnt[gi], kl, 64), b0 = __shfl(bbase[gi], kl, 64);
+                    const uint32_t run0 = tbl[k * TILE + al];
+                    for (uint32_t e0 = 0; e0 < nk; e0 += 64) {
+                        const uint32_t e = e0 + lane;
+                        const uint32_t mine = e < nk ? list[b0 + e] : 0xffffffffu;
+                        uint32_t rank = 0, e2 = 0;
+                        for (; e2 + 8 <= nk; e2 += 8) {
+                            uint32_t v[8];
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) v[u] = list[b0 + e2 + u];
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) rank += v[u] < mine ? 1u : 0u;
+                        }
+                        for (; e2 < nk; ++e2) rank += list[b0 + e2] < mine ? 1u : 0u;
+                        if (e < nk) {
+                            const uint32_t pos = run0 + rank;
+                            if (out_c) out_c[pos] = (int32_t)a;
+                            if (out_b) out_b[pos] = (int32_t)mine;
+                            if (out_k) out_k[pos] = k;
+                        }
+                    }
+                }
             }
         } else {
             // more neighbours than the list holds: rank each one by scanning the candidates again
@@ -299,6 +380,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
 }
@@ -440,7 +522,7 @@ size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, i
 }
 
 // Test hook: number of neighbours of one centre the fill pass keeps on chip before it falls back to
-// ranking by a second scan of the candidates (1..1024).  Not part of the public contract.
+// ranking by a second scan of the candidates (1..2048).  Not part of the public contract.
 int pcpp_debug_set_list_cap(int cap)
 {
     if (cap < 1 || cap > LIST_CAP_MAX) return PCPP_ERR_INVALID_ARG;
