@@ -257,6 +257,173 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict
 }
 
 // ---------------------------------------------------------------------------------------------
+// Rows kernel for wide layers (bf16, C_SRC a multiple of 64, large K): here W[k] is too large to be
+// re-read per 32 centres, so a block of eight waves owns 256 consecutive centres (32 per wave) and
+// shares every W[k] through LDS.  The work is a sequence of steps (cell k, 64-channel chunk c of the
+// source row); per step the block copies the 64 x C_DST slice of W[k] (fragment order, 16 B per lane)
+// into one of two LDS buffers while each wave gathers and sums the matching 128-byte slice of its
+// centres' source rows, then every wave multiplies its 32 x 64 tile with the shared slice.  One
+// barrier per step; cells without a triplet in the block's 256 centres are skipped by the whole block.
+//   packed W layout: piece ((((k*NCH + c)*NB + b)*4 + v)*64 + lane) =
+//                    W(k, dst = b*32 + lane%32, src = c*64 + (lane/32)*32 + v*8 .. +8)
+// ---------------------------------------------------------------------------------------------
+constexpr int BIG_WAVES = 8;
+
+template <int C_SRC, int C_DST, int J, typename TOut>
+__global__ __launch_bounds__(BIG_WAVES * 64) void rows_big_kernel(const void *__restrict__ feat_,
+                                                                  const void *__restrict__ w_, TOut *__restrict__ dst,
+                                                                  int64_t n_centres, int K,
+                                                                  const int32_t *__restrict__ gather,
+                                                                  uint32_t last_triplet, uint32_t feat_bytes,
+                                                                  PlanSideView side)
+{
+    constexpr uint32_t ROWB = C_SRC * 2;
+    constexpr int NCH = C_SRC / 64;                  // source chunks
+    constexpr int NB = C_DST / 32;                   // destination blocks
+    constexpr int PIECES = NB * 4 * 64;              // 16-byte pieces of one W slice
+    constexpr int PPT = PIECES / (BIG_WAVES * 64);   // pieces copied per thread
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // 2 * PIECES * 16 bytes
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int64_t blk = (int64_t)blockIdx.x * BIG_WAVES + wave;   // 32-centre block of this wave
+    const int64_t row0 = blk * ROWS;
+    const bool valid = row0 < n_centres;                          // wave-uniform
+    int64_t tile = blk >> 1;
+    if (tile >= side.n_tiles) tile = side.n_tiles - 1;
+    const int sub = (int)(blk & 1) * ROWS;
+    const bool last_in_tile = (sub + m) == TILE - 1;
+    const __amdgpu_buffer_rsrc_t frs = make_rsrc(feat_, feat_bytes);
+    const v4u *wsrc = static_cast<const v4u *>(w_) + threadIdx.x;
+    const uint32_t *runs = side.run_start + (size_t)tile * K * TILE + sub + m;
+    const uint32_t *tends = side.tile_ptr + tile + 1;
+    const int64_t t0 = (int64_t)blockIdx.x * (BIG_WAVES / 2);
+    const int64_t t1 = t0 + BIG_WAVES / 2 < side.n_tiles ? t0 + BIG_WAVES / 2 : side.n_tiles;
+
+    v16f acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[b][j] = 0.f;
+
+    int step = 0;
+    for (int k = 0; k < K; ++k) {
+        // any triplet of cell k among the block's centres?  (block-uniform)
+        if (side.tile_ptr[(size_t)k * side.n_tiles + t0] == side.tile_ptr[(size_t)k * side.n_tiles + t1]) continue;
+        uint32_t st_c = runs[(size_t)k * TILE];
+        uint32_t cn_c = (last_in_tile ? tends[(size_t)k * side.n_tiles] : runs[(size_t)k * TILE + 1]) - st_c;
+        if (!valid) cn_c = 0;
+        int32_t idx[J];
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const uint32_t p = st_c + j;
+            idx[j] = gather[p < last_triplet ? p : last_triplet];
+        }
+        const bool any = __ballot(cn_c != 0) != 0;
+#pragma unroll 1
+        for (int c = 0; c < NCH; ++c, ++step) {
+            char *buf = lds + (size_t)(step & 1) * PIECES * 16;
+            // this thread's share of the W slice
+            v4u wr[PPT];
+            const v4u *ws = wsrc + ((size_t)k * NCH + c) * PIECES;
+#pragma unroll
+            for (int q = 0; q < PPT; ++q) wr[q] = ws[q * BIG_WAVES * 64];
+            // the matching slice of this centre's source rows
+            const uint32_t slice_off = (uint32_t)(c * 64 + h * 32) * 2;
+            v4u rv[J][4];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const uint32_t off = (uint32_t)j < cn_c ? (uint32_t)idx[j] * ROWB + slice_off : OOB_OFFSET;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) rv[j][v] = buffer_load16(frs, off + v * 16);
+            }
+#pragma unroll
+            for (int q = 0; q < PPT; ++q)
+                *reinterpret_cast<v4u *>(buf + (size_t)(threadIdx.x + q * BIG_WAVES * 64) * 16) = wr[q];
+            float xs[32];
+#pragma unroll
+            for (int e = 0; e < 32; ++e) xs[e] = 0.f;
+            auto add_row = [&](const v4u (&r)[4]) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        xs[v * 8 + 2 * e] += __uint_as_float(r[v][e] << 16);
+                        xs[v * 8 + 2 * e + 1] += __uint_as_float(r[v][e] & 0xffff0000u);
+                    }
+            };
+#pragma unroll
+            for (int j = 0; j < J; ++j) add_row(rv[j]);
+            for (uint32_t j0 = J; j0 < cn_c; j0 += J) {           // runs longer than J
+                int32_t ix[J];
+#pragma unroll
+                for (int j = 0; j < J; ++j) {
+                    const uint32_t p = st_c + j0 + j;
+                    ix[j] = gather[p < last_triplet ? p : last_triplet];
+                }
+                v4u rr[J][4];
+#pragma unroll
+                for (int j = 0; j < J; ++j) {
+                    const uint32_t off = j0 + j < cn_c ? (uint32_t)ix[j] * ROWB + slice_off : OOB_OFFSET;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) rr[j][v] = buffer_load16(frs, off + v * 16);
+                }
+#pragma unroll
+                for (int j = 0; j < J; ++j) add_row(rr[j]);
+            }
+            v4u a[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[v][e] = pack_bf16x2(xs[v * 8 + 2 * e], xs[v * 8 + 2 * e + 1]);
+            __syncthreads();                                      // the slice is complete in LDS
+            if (any) {
+                const v4u *bl = reinterpret_cast<const v4u *>(buf) + lane;
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[v]),
+                                                                         __builtin_bit_cast(v8bf, bl[(b * 4 + v) * 64]),
+                                                                         acc[b], 0, 0, 0);
+            }
+        }
+    }
+    if (!valid) return;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
+            if (row < n_centres) {
+                if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + b * 32 + m] = acc[b][j];
+                else dst[(size_t)row * C_DST + b * 32 + m] = (uint16_t)(pack_bf16x2(acc[b][j], 0.f) & 0xffffu);
+            }
+        }
+}
+
+// W slices for rows_big_kernel (layout in its header comment)
+__global__ void pack_w_big_kernel(const uint16_t *__restrict__ w, uint16_t *__restrict__ packed, int K, int c_src,
+                                  int c_dst, int stride_d, int stride_s)
+{
+    const int nch = c_src / 64, nb = c_dst / 32;
+    const int64_t total = (int64_t)K * nch * nb * 4 * 64;
+    const int64_t piece = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (piece >= total) return;
+    const int lane = (int)(piece & 63);
+    int64_t r = piece >> 6;
+    const int v = (int)(r & 3); r >>= 2;
+    const int b = (int)(r % nb); r /= nb;
+    const int c = (int)(r % nch);
+    const int k = (int)(r / nch);
+    const int d = b * 32 + (lane & 31);
+    const int s0 = c * 64 + (lane >> 5) * 32 + v * 8;
+    const uint16_t *src = w + (size_t)k * c_dst * c_src + (size_t)d * stride_d;
+    uint16_t *dstp = packed + piece * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dstp[e] = src[(size_t)(s0 + e) * stride_s];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Weight gradient (VVOR), Eq. (5).  Wave c owns triplets [c*chunk, (c+1)*chunk) of the (k, o, i)
 // ordered list.  A chunk usually lies inside one cell's run; where a run starts inside the chunk the
 // accumulator is flushed and restarted.  Slots of the partial buffer:
@@ -266,7 +433,9 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict
 // triplet 2 s + h.  bf16: one step consumes 16 triplets; a lane reads one dword (2 channels) per
 // triplet and the even / odd channels form separate 32-wide blocks of the operand.
 // ---------------------------------------------------------------------------------------------
-template <bool BF16, int C_IN, int C_OUT>
+// Wide layers: a wave owns a SUB_OUT x SUB_IN block of dW[k]; the n_sub waves that share a chunk are
+// consecutive, so their re-reads of the same rows are served by the L1 / L2 caches.
+template <bool BF16, int C_IN, int C_OUT, int SUB_IN, int SUB_OUT>
 __global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
                                                             float *__restrict__ part,
                                                             const int32_t *__restrict__ tri_o,
@@ -274,12 +443,16 @@ __global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restri
                                                             const int64_t *__restrict__ seg, int K, int64_t n_triplets,
                                                             int chunk, int64_t n_chunks)
 {
-    constexpr int NBI = C_IN / 32, NBO = C_OUT / 32;
+    constexpr int NBI = SUB_IN / 32, NBO = SUB_OUT / 32;
+    constexpr int N_SUB_IN = C_IN / SUB_IN, N_SUB = N_SUB_IN * (C_OUT / SUB_OUT);
     constexpr int STEP = BF16 ? 16 : 2;      // triplets per MFMA step
     constexpr int NS = 32 / STEP;            // steps per batch of 32 triplets
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
-    const int64_t chunk_id = (int64_t)blockIdx.x * WAVES + wave;
+    const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
+    const int64_t chunk_id = gw / N_SUB;
+    const int sub = (int)(gw % N_SUB);
+    const int ci0 = (sub % N_SUB_IN) * SUB_IN, co0 = (sub / N_SUB_IN) * SUB_OUT;
     if (chunk_id >= n_chunks) return;
     int64_t p = chunk_id * chunk;
     int64_t p_end = p + chunk;
@@ -318,8 +491,8 @@ __global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restri
                 for (int s = 0; s < NS; ++s) {
                     const int t = 2 * s + h;
                     const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
-                    const float *dyr = static_cast<const float *>(dy_) + (size_t)o * C_OUT + c;
-                    const float *xr = static_cast<const float *>(x_) + (size_t)i * C_IN + c;
+                    const float *dyr = static_cast<const float *>(dy_) + (size_t)o * C_OUT + co0 + c;
+                    const float *xr = static_cast<const float *>(x_) + (size_t)i * C_IN + ci0 + c;
 #pragma unroll
                     for (int bo = 0; bo < NBO; ++bo) a[bo][s] = t < n ? dyr[bo * 32] : 0.f;
 #pragma unroll
@@ -334,7 +507,7 @@ __global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restri
                             acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bo][s], b[bi][s], acc[bo][bi], 0, 0, 0);
             } else {
                 // block index of the operand = 2 * q + parity: channel 2 * (c + 32 q) + parity
-                constexpr int QO = C_OUT / 64, QI = C_IN / 64;
+                constexpr int QO = SUB_OUT / 64, QI = SUB_IN / 64;
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
                     uint32_t dyw[QO][8], xw[QI][8];
@@ -342,8 +515,8 @@ __global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restri
                     for (int e = 0; e < 8; ++e) {
                         const int t = 16 * s + 8 * h + e;
                         const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
-                        const uint32_t *dyr = static_cast<const uint32_t *>(dy_) + (size_t)o * (C_OUT / 2) + c;
-                        const uint32_t *xr = static_cast<const uint32_t *>(x_) + (size_t)i * (C_IN / 2) + c;
+                        const uint32_t *dyr = static_cast<const uint32_t *>(dy_) + (size_t)o * (C_OUT / 2) + co0 / 2 + c;
+                        const uint32_t *xr = static_cast<const uint32_t *>(x_) + (size_t)i * (C_IN / 2) + ci0 / 2 + c;
 #pragma unroll
                         for (int qo = 0; qo < QO; ++qo) dyw[qo][e] = t < n ? dyr[qo * 32] : 0u;
 #pragma unroll
@@ -385,11 +558,11 @@ __global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restri
                     const int r = 8 * (j / 4) + 4 * h + (j % 4);
                     int co, ci;
                     if constexpr (BF16) {
-                        co = 2 * (r + 32 * (bo >> 1)) + (bo & 1);
-                        ci = 2 * (c + 32 * (bi >> 1)) + (bi & 1);
+                        co = co0 + 2 * (r + 32 * (bo >> 1)) + (bo & 1);
+                        ci = ci0 + 2 * (c + 32 * (bi >> 1)) + (bi & 1);
                     } else {
-                        co = bo * 32 + r;
-                        ci = bi * 32 + c;
+                        co = co0 + bo * 32 + r;
+                        ci = ci0 + bi * 32 + c;
                     }
                     dstp[(size_t)co * C_IN + ci] = acc[bo][bi][j];
                 }
@@ -427,21 +600,24 @@ __global__ __launch_bounds__(256) void weight_reduce(const float *__restrict__ p
     }
 }
 
-// triplets per wave: at least 512, grown so that there are at most about 8192 chunks
-int weight_chunk(int64_t n_triplets)
+// triplets per chunk: at least 512, grown so that there are at most about 8192 chunks (2048 for wide
+// layers, whose partial sums are large)
+int weight_chunk(int64_t n_triplets, int c_in, int c_out)
 {
+    const int64_t max_chunks = (int64_t)c_in * c_out >= 128 * 128 ? 2048 : 8192;
     int chunk = 512;
-    while ((n_triplets + chunk - 1) / chunk > 8192) chunk *= 2;
+    while ((n_triplets + chunk - 1) / chunk > max_chunks) chunk *= 2;
     return chunk;
 }
 
-template <bool BF16, int C_IN, int C_OUT>
+template <bool BF16, int C_IN, int C_OUT, int SUB_IN = C_IN, int SUB_OUT = C_OUT>
 int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int64_t *seg, void *workspace,
                   size_t workspace_bytes, hipStream_t stream)
 {
     const int n_elem = C_IN * C_OUT;
-    const int chunk = weight_chunk(a.n_triplets);
+    const int chunk = weight_chunk(a.n_triplets, C_IN, C_OUT);
     const int64_t n_chunks = ceil_div(a.n_triplets, chunk);
+    constexpr int N_SUB = (C_IN / SUB_IN) * (C_OUT / SUB_OUT);
     const size_t need = (size_t)(n_chunks + a.K) * n_elem * sizeof(float);
     if (workspace_bytes < need) {
         set_error("pcpp_mvmr_bwd_weight: workspace has %zu bytes, needs %zu", workspace_bytes, need);
@@ -449,7 +625,7 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     }
     float *part = static_cast<float *>(workspace);
     if (n_chunks > 0) {
-        weight_kernel<BF16, C_IN, C_OUT><<<(unsigned)ceil_div(n_chunks, WAVES), WAVES * 64, 0, stream>>>(
+        weight_kernel<BF16, C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
             a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
         PCPP_HIP_CHECK(hipGetLastError());
     }
@@ -462,7 +638,8 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
 bool weight_shape_supported(int in_dtype, int c_in, int c_out)
 {
     if (in_dtype == PCPP_F32) return (c_in == 32 && c_out == 32) || (c_in == 64 && c_out == 64);
-    return (c_in == 64 && c_out == 64) || (c_in == 64 && c_out == 128) || (c_in == 128 && c_out == 128);
+    return (c_in == 64 && c_out == 64) || (c_in == 64 && c_out == 128) || (c_in == 128 && c_out == 128) ||
+           (c_in == 256 && c_out == 256);
 }
 
 template <bool BF16, int C_SRC, int C_DST, int J, int KW>
@@ -496,9 +673,42 @@ int launch_rows(const MvmrArgs &a, hipStream_t stream, bool *handled)
 
 }  // namespace
 
+// wide bf16 layers with any K: rows_big_kernel
+bool rows_big_shape(const MvmrArgs &a)
+{
+    return a.in_dtype == PCPP_BF16 && ((a.c_src == 256 && a.c_dst == 256) || (a.c_src == 128 && a.c_dst == 128));
+}
+
+template <int C_SRC, int C_DST>
+int launch_rows_big(const MvmrArgs &a, hipStream_t stream)
+{
+    constexpr int J = 2;
+    const int64_t blocks = ceil_div(ceil_div(a.n_centres, ROWS), BIG_WAVES);
+    const size_t lds = (size_t)2 * (C_DST / 32) * 4 * 64 * 16;
+    const uint32_t last = (uint32_t)(a.n_triplets - 1);
+    const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * 2);
+    if (a.out_dtype == PCPP_F32) {
+        auto kern = rows_big_kernel<C_SRC, C_DST, J, float>;
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        kern<<<(unsigned)blocks, BIG_WAVES * 64, lds, stream>>>(a.feat, a.w, static_cast<float *>(a.dst), a.n_centres,
+                                                                a.K, a.gather, last, feat_bytes, a.side);
+    } else {
+        auto kern = rows_big_kernel<C_SRC, C_DST, J, uint16_t>;
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        kern<<<(unsigned)blocks, BIG_WAVES * 64, lds, stream>>>(a.feat, a.w, static_cast<uint16_t *>(a.dst),
+                                                                a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+    }
+    PCPP_HIP_CHECK(hipGetLastError());
+    return PCPP_OK;
+}
+
 bool mvmr_rows_mfma_supported(const MvmrArgs &a)
 {
-    if (a.n_triplets <= 0 || a.K > 28) return false;
+    if (a.n_triplets <= 0) return false;
+    if (rows_big_shape(a)) return (size_t)a.n_src * a.c_src * 2 <= MAX_BUFFER_BYTES;
+    if (a.K > 28) return false;
     const size_t es = a.in_dtype == PCPP_BF16 ? 2 : 4;
     if ((size_t)a.n_src * a.c_src * es > MAX_BUFFER_BYTES) return false;
     if (a.in_dtype == PCPP_F32 && a.out_dtype == PCPP_F32)
@@ -516,6 +726,12 @@ int mvmr_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int st
     const int e = dtype == PCPP_BF16 ? 8 : 4;
     const int64_t total = (int64_t)K * (c_dst / 32) * (c_src / 2 / e) * 64;
     const unsigned blocks = (unsigned)ceil_div(total, 256);
+    if (dtype == PCPP_BF16 && ((c_src == 256 && c_dst == 256) || (c_src == 128 && c_dst == 128))) {
+        pack_w_big_kernel<<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w), static_cast<uint16_t *>(packed),
+                                                      K, c_src, c_dst, stride_d, stride_s);
+        PCPP_HIP_CHECK(hipGetLastError());
+        return PCPP_OK;
+    }
     if (dtype == PCPP_BF16)
         pack_w_kernel<uint16_t><<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w),
                                                             static_cast<uint16_t *>(packed), K, c_src, c_dst,
@@ -532,6 +748,10 @@ int mvmr_rows_mfma(const MvmrArgs &a, hipStream_t stream, bool *handled)
 {
     *handled = true;
     if (!mvmr_rows_mfma_supported(a)) { *handled = false; return PCPP_OK; }
+    if (rows_big_shape(a)) {
+        if (a.c_src == 256) return launch_rows_big<256, 256>(a, stream);
+        return launch_rows_big<128, 128>(a, stream);
+    }
     if (a.in_dtype == PCPP_F32 && a.out_dtype == PCPP_F32) {
         if (a.c_src == 32 && a.c_dst == 32) return launch_rows<false, 32, 32, 2>(a, stream, handled);
         if (a.c_src == 16 && a.c_dst == 32) return launch_rows<false, 16, 32, 2>(a, stream, handled);
@@ -557,7 +777,8 @@ int mvmr_weight_mfma(const MvmrArgs &a, float *dw, const int32_t *tri_o, const i
     } else {
         if (a.c_src == 64 && a.c_dst == 64) return launch_weight<true, 64, 64>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
         if (a.c_src == 64 && a.c_dst == 128) return launch_weight<true, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
-        if (a.c_src == 128 && a.c_dst == 128) return launch_weight<true, 128, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 128 && a.c_dst == 128) return launch_weight<true, 128, 128, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 256 && a.c_dst == 256) return launch_weight<true, 256, 256, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
     }
     *handled = false;
     return PCPP_OK;
@@ -566,7 +787,7 @@ int mvmr_weight_mfma(const MvmrArgs &a, float *dw, const int32_t *tri_o, const i
 size_t mvmr_weight_mfma_workspace_bytes(int64_t n_triplets, int c_in, int c_out, int K, int in_dtype)
 {
     if (!weight_shape_supported(in_dtype, c_in, c_out)) return 0;
-    const int chunk = weight_chunk(n_triplets);
+    const int chunk = weight_chunk(n_triplets, c_in, c_out);
     return align_up((size_t)(ceil_div(n_triplets, chunk) + K) * c_in * c_out * sizeof(float));
 }
 

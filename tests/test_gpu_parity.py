@@ -84,6 +84,9 @@ def test_scene_full(pcpp, sid):
     dict(n_in=2100, n_out=700, r=0.15, t=3, cin=64, cout=128, dt="bf16"),
     dict(n_in=999, n_out=999, r=0.2, t=5, cin=32, cout=32, dt="bf16"),
     dict(n_in=800, n_out=31, r=0.2, t=2, cin=64, cout=64, dt="f32"),
+    # wide layers (W shared through LDS), K = 125 and K = 27, ragged point counts
+    dict(n_in=1500, n_out=1300, r=0.15, t=5, cin=256, cout=256, dt="bf16"),
+    dict(n_in=700, n_out=900, r=0.2, t=3, cin=128, cout=128, dt="bf16"),
 ])
 def test_small_shapes(pcpp, case):
     """Ragged sizes: n_out != n_in, partial tiles, channel counts that are not multiples of anything."""
@@ -190,3 +193,60 @@ def test_determinism(pcpp):
                      gx.cpu().numpy(), gw.cpu().numpy()])
     for a, b in zip(*outs):
         assert np.array_equal(a, b)
+
+
+def test_scene5_full_size_sampled(pcpp):
+    """Scene 5 (1M points, K = 125, 256 -> 256 bf16) at full size.  The oracle cannot finish the whole scene
+    in a test, so: global invariants of the triplet list, bit-exact triplets for sampled outputs (and, with the
+    roles swapped, for sampled inputs), and every float op on those samples element by element."""
+    s = scenes.make_scene(5)
+    x, w, dy = scenes.make_features(s)
+    tol = TOL[s.dtype]
+    rng = np.random.default_rng(55)
+    xyz = dev(s.in_xyz)
+    T = pcpp.pcpp_build_triplets(xyz, xyz, s.radius, s.t)
+    n = s.n_in
+    # invariants on the whole list
+    assert T.n_triplets == pcpp.binding.pcpp_count_triplets(xyz, xyz, s.radius, s.t)
+    key = (T.tri_k.long() * n + T.tri_o.long()) * n + T.tri_i.long()
+    assert bool((key[1:] > key[:-1]).all())                       # strictly ascending (k, o, i)
+    seg = T.seg_offsets.cpu().numpy()
+    assert seg[0] == 0 and seg[-1] == T.n_triplets
+    bounds = torch.searchsorted(T.tri_k.long().contiguous(), torch.arange(s.K + 1, device="cuda"))
+    assert np.array_equal(bounds.cpu().numpy(), seg)
+    cnt = np.diff(seg).reshape(5, 5, 5)
+    assert all(cnt[a, b, c] == 0 for a in (0, 4) for b in (0, 4) for c in (0, 4))   # corner cells lie outside the ball
+    assert abs(T.n_triplets / n - 32.0) <= 1.0
+    del key
+    tri_o, tri_i, tri_k = (t.cpu().numpy() for t in (T.tri_o, T.tri_i, T.tri_k))
+
+    # sampled outputs: triplets and forward
+    so = np.sort(rng.choice(n, 4096, replace=False))
+    o, i, k, _ = oracle.build_triplets(s.in_xyz, s.out_xyz[so], s.radius, s.t)
+    sel = np.isin(tri_o, so)
+    assert np.array_equal(np.searchsorted(so, tri_o[sel]), o)
+    assert np.array_equal(tri_i[sel], i) and np.array_equal(tri_k[sel], k)
+    dt = feat_dtype(s)
+    dx_, dw_, ddy = dev(x, dt), dev(w, dt), dev(dy, dt)
+    out = pcpp.pcpp_mvmr_fwd(dx_, dw_, T)
+    ui, inv = np.unique(i, return_inverse=True)
+    ref, scale = oracle_fwd(x[ui], w, o, inv.astype(np.int32), k, len(so))
+    assert_close(out[torch.from_numpy(so).cuda()].cpu().numpy(), ref, scale, tol, "scene5 fwd (sampled outputs)")
+    # weight gradient with dy restricted to the sampled outputs: only their triplets contribute
+    dy_m = np.zeros_like(dy)
+    dy_m[so] = dy[so]
+    gw = pcpp.pcpp_mvmr_bwd_weight(dx_, dev(dy_m, dt), T).cpu().numpy()
+    ref, scale = oracle_bwd_weight(x[ui], dy[so], o, inv.astype(np.int32), k, s.K)
+    assert_close(gw, ref, scale, tol, "scene5 bwd_weight (dy on sampled outputs)")
+    del out, gw
+
+    # sampled inputs: all triplets that touch them, and the input gradient
+    si = np.sort(rng.choice(n, 4096, replace=False))
+    o2, i2, k2, _ = oracle.build_triplets(s.in_xyz[si], s.out_xyz, s.radius, s.t)
+    sel = np.isin(tri_i, si)
+    got = sorted(zip(tri_k[sel].tolist(), tri_o[sel].tolist(), np.searchsorted(si, tri_i[sel]).tolist()))
+    assert got == sorted(zip(k2.tolist(), o2.tolist(), i2.tolist()))
+    gx = pcpp.pcpp_mvmr_bwd_input(ddy, dw_, T)
+    uo, inv = np.unique(o2, return_inverse=True)
+    ref, scale = oracle_bwd_input(dy[uo], w, inv.astype(np.int32), i2, k2, len(si))
+    assert_close(gx[torch.from_numpy(si).cuda()].cpu().numpy(), ref, scale, tol, "scene5 bwd_input (sampled inputs)")
