@@ -20,6 +20,7 @@ SOURCES = {
     "build_triplets.hip": ["-ffp-contract=off"],
     "mvmr_generic.hip": [],
     "mvmr_mfma.hip": [],
+    "mvmr_rows.hip": [],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -17,9 +17,9 @@ namespace {
 constexpr unsigned long long EMPTY_KEY = ~0ull;
 constexpr int CELL_BIAS = 1 << 20;
 constexpr double CELL_CLAMP = (double)((1 << 20) - 2);   // +-1 stencil steps stay inside 21 bits
-constexpr int SEARCH_THREADS = 256;
+constexpr int SEARCH_THREADS = 1024;                      // 16 waves share a tile of 64 centres: 4 centres each
 constexpr int SEARCH_WAVES = SEARCH_THREADS / 64;
-constexpr int LIST_CAP_MAX = 2048;                        // neighbours of one centre kept in LDS
+constexpr int LIST_CAP_MAX = 512;                         // neighbours of one centre kept in LDS (per wave)
 
 __device__ inline uint32_t hash_key(unsigned long long k)
 {
@@ -522,7 +522,7 @@ size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, i
 }
 
 // Test hook: number of neighbours of one centre the fill pass keeps on chip before it falls back to
-// ranking by a second scan of the candidates (1..2048).  Not part of the public contract.
+// ranking by a second scan of the candidates (1..512).  Not part of the public contract.
 int pcpp_debug_set_list_cap(int cap)
 {
     if (cap < 1 || cap > LIST_CAP_MAX) return PCPP_ERR_INVALID_ARG;

@@ -18,6 +18,8 @@
 // is cut into equal chunks, one per wave; the reduction index of the MFMA is the triplet, both
 // operands are rows read straight from memory (lane <-> channel), partial sums per chunk go to the
 // workspace and are added in a fixed order by a second kernel.
+#include <stdlib.h>
+
 #include "pcpp_internal.h"
 
 namespace pcpp {
@@ -89,18 +91,18 @@ __global__ void pack_w_kernel(const T *__restrict__ w, T *__restrict__ packed, i
 
 // KW = kernel cells per wave (compile time): the cell loop is fully unrolled so that the run bounds and
 // the first J gather indices of every cell are fetched up front, leaving one memory round trip per cell.
-template <bool BF16, int C_SRC, int C_DST, int J, int KW, typename TOut>
-__global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
+template <bool BF16, int C_SRC, int C_DST, int J, int KW, bool PIPE, int NW, typename TOut>
+__global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
                                                           TOut *__restrict__ dst, int64_t n_centres, int K,
                                                           const int32_t *__restrict__ gather, uint32_t last_triplet,
-                                                          uint32_t feat_bytes, PlanSideView side)
+                                                          uint32_t feat_bytes, PlanSideView side, int dbg)
 {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr uint32_t ROWB = C_SRC * ES;    // bytes per source row
     constexpr int HALF = C_SRC / 2;          // channels per lane
     constexpr int NV = HALF * ES / 16;       // 16-byte loads per source row per lane
     constexpr int NB = C_DST / 32;           // 32-wide destination blocks
-    extern __shared__ float red[];           // [WAVES - 1][NB * 16][64]
+    extern __shared__ float red[];           // [NW - 1][NB * 16][64]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
     const int64_t blk = blockIdx.x;          // 32-centre block
@@ -119,21 +121,21 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict
     uint32_t st[KW], cn[KW];
 #pragma unroll
     for (int t = 0; t < KW; ++t) {
-        const int k = wave + WAVES * t;
+        const int k = wave + NW * t;
         const int kc = k < K ? k : K - 1;
         const uint32_t *pe = last_in_tile ? tends + (size_t)kc * side.n_tiles : runs + (size_t)kc * TILE + 1;
-        st[t] = runs[(size_t)kc * TILE];
-        cn[t] = *pe;
+        st[t] = (dbg & 8) ? 0u : runs[(size_t)kc * TILE];
+        cn[t] = (dbg & 8) ? 0u : *pe;
     }
 #pragma unroll
-    for (int t = 0; t < KW; ++t) cn[t] = (wave + WAVES * t) < K ? cn[t] - st[t] : 0u;
+    for (int t = 0; t < KW; ++t) cn[t] = (wave + NW * t) < K ? cn[t] - st[t] : 0u;
     int32_t idx[KW][J];
 #pragma unroll
     for (int t = 0; t < KW; ++t)
 #pragma unroll
         for (int j = 0; j < J; ++j) {
             const uint32_t p = st[t] + j;
-            idx[t][j] = gather[p < last_triplet ? p : last_triplet];
+            idx[t][j] = (dbg & 8) ? 0 : gather[p < last_triplet ? p : last_triplet];
         }
     // keep the index loads here, ahead of the cell loop (they would otherwise be sunk next to their uses)
 #pragma unroll
@@ -150,27 +152,32 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict
     // Two cells in flight: the loads of cell t+1 (W fragments and the first J rows of every run) are
     // issued before the rows of cell t are consumed.  Lanes past the end of their run read through an
     // out-of-range buffer offset (zeros, no traffic), so the issue step has no branches.
-    v4u bw[2][NB][NV];
-    v4u rv[2][J][NV];
+    v4u bw[PIPE ? 2 : 1][NB][NV];
+    v4u rv[PIPE ? 2 : 1][J][NV];
     auto issue = [&](int t, int buf) {
-        const int k = wave + WAVES * t;
+        const int k = wave + NW * t;
         const int kc = k < K ? k : K - 1;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int v = 0; v < NV; ++v) bw[buf][b][v] = wfrag[(((size_t)kc * NB + b) * NV + v) * 64];
+            for (int v = 0; v < NV; ++v)
+                bw[buf][b][v] = (dbg & 16) ? v4u{1u, 2u, 3u, 4u} : wfrag[(((size_t)((dbg & 2) ? 0 : kc) * NB + b) * NV + v) * 64];
 #pragma unroll
         for (int j = 0; j < J; ++j) {
-            const uint32_t off = (uint32_t)j < cn[t] ? (uint32_t)idx[t][j] * ROWB + lane_off : OOB_OFFSET;
+            const uint32_t off = ((uint32_t)j < cn[t] && !(dbg & 1)) ? (uint32_t)idx[t][j] * ROWB + lane_off : OOB_OFFSET;
 #pragma unroll
             for (int v = 0; v < NV; ++v) rv[buf][j][v] = buffer_load16(frs, off + v * 16);
         }
     };
-    issue(0, 0);
+    if constexpr (PIPE) issue(0, 0);
 #pragma unroll
     for (int t = 0; t < KW; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < KW) issue(t + 1, buf ^ 1);
+        const int buf = PIPE ? (t & 1) : 0;
+        if constexpr (PIPE) {
+            if (t + 1 < KW) issue(t + 1, buf ^ 1);
+        } else {
+            issue(t, 0);
+        }
         const uint32_t cn_c = cn[t], st_c = st[t];
         float xs[HALF];
 #pragma unroll
@@ -208,6 +215,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict
 #pragma unroll
             for (int j = 0; j < J; ++j) add_row(rr[j]);
         }
+        if (dbg & 4) { acc[0][0] += xs[0] + __uint_as_float(bw[buf][0][0][0]); continue; }
         if constexpr (BF16) {
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
@@ -247,7 +255,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const void *__restrict
         for (int j = 0; j < 16; ++j) {
             float v = acc[b][j];
 #pragma unroll
-            for (int wv = 0; wv < WAVES - 1; ++wv) v += red[((size_t)wv * NB * 16 + b * 16 + j) * 64 + lane];
+            for (int wv = 0; wv < NW - 1; ++wv) v += red[((size_t)wv * NB * 16 + b * 16 + j) * 64 + lane];
             const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
             if (row < n_centres) {
                 if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + b * 32 + m] = v;
@@ -642,22 +650,39 @@ bool weight_shape_supported(int in_dtype, int c_in, int c_out)
            (c_in == 256 && c_out == 256);
 }
 
-template <bool BF16, int C_SRC, int C_DST, int J, int KW>
-int launch_rows_kw(const MvmrArgs &a, hipStream_t stream)
+int rows_env(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : dflt;
+}
+
+template <bool BF16, int C_SRC, int C_DST, int J, int KW, bool PIPE, int NW>
+int launch_rows_cfg(const MvmrArgs &a, hipStream_t stream)
 {
     const int64_t blocks = ceil_div(a.n_centres, ROWS);
-    const size_t lds = (size_t)(WAVES - 1) * (C_DST / 32) * 16 * 64 * sizeof(float);
+    const size_t lds = (size_t)(NW - 1) * (C_DST / 32) * 16 * 64 * sizeof(float);
     const uint32_t last = (uint32_t)(a.n_triplets - 1);
     const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * (BF16 ? 2 : 4));
     if (a.out_dtype == PCPP_F32) {
-        rows_kernel<BF16, C_SRC, C_DST, J, KW, float><<<(unsigned)blocks, WAVES * 64, lds, stream>>>(
-            a.feat, a.w, static_cast<float *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+        rows_kernel<BF16, C_SRC, C_DST, J, KW, PIPE, NW, float><<<(unsigned)blocks, NW * 64, lds, stream>>>(
+            a.feat, a.w, static_cast<float *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side, rows_env("PCPP_ROWS_DBG", 0));
     } else {
-        rows_kernel<BF16, C_SRC, C_DST, J, KW, uint16_t><<<(unsigned)blocks, WAVES * 64, lds, stream>>>(
-            a.feat, a.w, static_cast<uint16_t *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+        rows_kernel<BF16, C_SRC, C_DST, J, KW, PIPE, NW, uint16_t><<<(unsigned)blocks, NW * 64, lds, stream>>>(
+            a.feat, a.w, static_cast<uint16_t *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side, rows_env("PCPP_ROWS_DBG", 0));
     }
     PCPP_HIP_CHECK(hipGetLastError());
     return PCPP_OK;
+}
+
+// K <= 28: either 4 waves x 7 cells or 8 waves x 4 cells per 32-centre block
+template <bool BF16, int C_SRC, int C_DST, int J>
+int launch_rows_k28(const MvmrArgs &a, hipStream_t stream)
+{
+    static const int nw = rows_env("PCPP_ROWS_NW", 4), pipe = rows_env("PCPP_ROWS_PIPE", 0);
+    if (nw == 8) return pipe ? launch_rows_cfg<BF16, C_SRC, C_DST, J, 4, true, 8>(a, stream)
+                             : launch_rows_cfg<BF16, C_SRC, C_DST, J, 4, false, 8>(a, stream);
+    return pipe ? launch_rows_cfg<BF16, C_SRC, C_DST, J, 7, true, 4>(a, stream)
+                : launch_rows_cfg<BF16, C_SRC, C_DST, J, 7, false, 4>(a, stream);
 }
 
 // cells per wave: 7 covers K <= 28 (t <= 3); larger kernels fall back to the generic path
@@ -665,8 +690,8 @@ template <bool BF16, int C_SRC, int C_DST, int J>
 int launch_rows(const MvmrArgs &a, hipStream_t stream, bool *handled)
 {
     if ((size_t)a.n_src * C_SRC * (BF16 ? 2 : 4) > MAX_BUFFER_BYTES) { *handled = false; return PCPP_OK; }
-    if (a.K <= 4 * 2) return launch_rows_kw<BF16, C_SRC, C_DST, J, 2>(a, stream);
-    if (a.K <= 4 * 7) return launch_rows_kw<BF16, C_SRC, C_DST, J, 7>(a, stream);
+    if (a.K <= 4 * 2) return launch_rows_cfg<BF16, C_SRC, C_DST, J, 2, false, 4>(a, stream);
+    if (a.K <= 4 * 7) return launch_rows_k28<BF16, C_SRC, C_DST, J>(a, stream);
     *handled = false;
     return PCPP_OK;
 }

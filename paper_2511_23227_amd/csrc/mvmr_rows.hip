@@ -1,0 +1,356 @@
+// MVMR rows kernel (Eq. (1) forward; Sec. 3.3.3 input gradient with W^T) for K <= 28 on the matrix cores.
+//
+// Eq. (1) is linear, so out[o] = sum_k W[k] S_k[o] with S_k[o] = sum of x[i] over the (k, o) run.  Both
+// factors of that expression are matrix products and both run on the MFMA units:
+//
+//   stage 1 (sum of each run)   S_k^T [channel][centre] = X_g^T [channel][triplet] . Sel^T [triplet][centre]
+//       X_g = the source rows of the (cell, 32-centre block) run, one row per triplet, read densely
+//       (a half-wave reads one 128-byte row, lane <-> channel); Sel[centre][triplet] = 1 when the triplet
+//       belongs to the centre's run, built in registers from the run bounds.  Products with 1.0 are exact,
+//       so this is the fp32 sum of the rows; run lengths never cause divergence and every loaded byte
+//       is used.  fp32 inputs are split exactly into three bf16 terms (8 + 8 + 8 significant bits).
+//   stage 2 (Eq. (1))           acc [centre][c_dst] += S_k [centre][channel] . W[k]^T
+//       The stage-1 accumulator layout (lane <-> centre, register <-> channel) is the A-operand layout of
+//       the second MFMA up to a permutation of the reduction index, which is folded into the order in
+//       which W is packed.  bf16: the fp32 sums are rounded to bf16 once (v_cvt_pk_bf16_f32).
+//
+// A block of NW waves owns 32 consecutive centres and all destination channels; wave w takes cells
+// w, w + NW, ...; the partial accumulators are added in wave order through LDS and every destination
+// row is written once: no atomics, fixed summation order.
+//
+// MFMA layouts (wave64), v_mfma_f32_32x32x16_bf16: A: lane (M = l%32, h = l/32) holds A[M][8h .. 8h+7];
+// B: lane (N = l%32, h) holds B[8h .. 8h+7][N]; D: lane l, register j -> M = 8*(j/4) + 4*(l/32) + j%4, N = l%32.
+// v_mfma_f32_32x32x2_f32: A: lane (M, h) holds A[M][h]; B: lane (N, h) holds B[h][N]; D as above.
+#include "pcpp_internal.h"
+
+namespace pcpp {
+
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+constexpr int ROWS = 32;                         // centres per block
+constexpr uint32_t OOB_OFFSET = 0xffffff00u;     // buffer offset past any descriptor: reads zero, no traffic
+constexpr size_t MAX_BUFFER_BYTES = 0xfffff000u;
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ inline uint32_t cvt_pk_bf16(float lo, float hi)
+{
+    const v2f v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf));   // round to nearest even
+}
+
+// Source channel of element e of packed piece pc for lane-half h (see the header comment and rows_kernel).
+//   fp32: piece pc = g*4 + v      : 4 floats, channel 32 g + 8 v + 4 h + e
+//   bf16: piece pc = (g*2+par)*2+s: 8 bf16, dword column d = 32 g + 8 (2 s + e/4) + 4 h + e%4, channel 2 d + par
+template <bool BF16>
+__host__ __device__ inline int packed_channel(int pc, int h, int e)
+{
+    if constexpr (BF16) {
+        const int s = pc & 1, par = (pc >> 1) & 1, g = pc >> 2;
+        const int d = 32 * g + 8 * (2 * s + (e >> 2)) + 4 * h + (e & 3);
+        return 2 * d + par;
+    } else {
+        const int v = pc & 3, g = pc >> 2;
+        return 32 * g + 8 * v + 4 * h + e;
+    }
+}
+
+// packed[(((k*NB + b)*NPC + pc)*64 + lane)*16 bytes] = W(k, dst = b*32 + lane%32, src = packed_channel(pc, lane/32, e))
+// with W(k, d, s) read at w[k*c_dst*c_src + d*stride_d + s*stride_s] (covers W as stored and its transpose).
+template <typename T>
+__global__ void pack_w_sel_kernel(const T *__restrict__ w, T *__restrict__ packed, int K, int c_src, int c_dst,
+                                  int stride_d, int stride_s)
+{
+    constexpr bool BF16 = sizeof(T) == 2;
+    constexpr int E = 16 / sizeof(T);
+    const int nb = c_dst / 32, npc = c_src / E / 2;   // pieces per (k, b): every lane-half covers c_src / 2 channels
+    const int64_t total = (int64_t)K * nb * npc * 64;
+    const int64_t piece = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (piece >= total) return;
+    const int lane = (int)(piece & 63);
+    int64_t r = piece >> 6;
+    const int pc = (int)(r % npc); r /= npc;
+    const int b = (int)(r % nb);
+    const int k = (int)(r / nb);
+    const int d = b * 32 + (lane & 31);
+    const T *src = w + (size_t)k * c_dst * c_src + (size_t)d * stride_d;
+    T *dst = packed + piece * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) dst[e] = src[(size_t)packed_channel<BF16>(pc, lane >> 5, e) * stride_s];
+}
+
+template <bool BF16, int C_SRC, int C_DST, int KW, int NW, typename TOut>
+__global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
+                                                       TOut *__restrict__ dst, int64_t n_centres, int K,
+                                                       const int32_t *__restrict__ gather, uint32_t last_triplet,
+                                                       uint32_t feat_bytes, PlanSideView side)
+{
+    constexpr int DW = BF16 ? C_SRC / 2 : C_SRC;     // dwords per source row
+    constexpr int NG = DW / 32;                      // lane c reads dword columns c + 32 g
+    constexpr int NP = BF16 ? 2 : 1;                 // even / odd channel of a dword (bf16)
+    constexpr int NS1 = NG * NP;                     // stage-1 accumulator blocks of 32 channels
+    constexpr int NB = C_DST / 32;                   // destination blocks
+    constexpr int NPC = BF16 ? NS1 * 2 : NG * 4;     // packed W pieces per (cell, destination block)
+    constexpr uint32_t ROWB = DW * 4;
+    extern __shared__ float red[];                   // [NW - 1][NB * 16][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;          // c: channel column in stage 1, centre in stage 2
+    const int64_t blk = blockIdx.x;
+    const int64_t row0 = blk * ROWS;
+    const int64_t tile = blk >> 1;
+    const int sub = (int)(blk & 1) * ROWS;           // offset of the block inside its 64-centre tile
+    const bool last_in_tile = (sub + c) == TILE - 1;
+    const __amdgpu_buffer_rsrc_t frs = make_rsrc(feat_, feat_bytes);
+    const v4u *wfrag = static_cast<const v4u *>(w_) + lane;
+    const uint32_t *runs = side.run_start + (size_t)tile * K * TILE + sub + c;
+    const uint32_t *tends = side.tile_ptr + tile + 1;
+
+    // run bounds of centre c for this wave's cells
+    uint32_t st[KW], cn[KW];
+#pragma unroll
+    for (int t = 0; t < KW; ++t) {
+        const int k = wave + NW * t;
+        const int kc = k < K ? k : K - 1;
+        const uint32_t *pe = last_in_tile ? tends + (size_t)kc * side.n_tiles : runs + (size_t)kc * TILE + 1;
+        st[t] = runs[(size_t)kc * TILE];
+        cn[t] = *pe;
+    }
+    // the block's run in cell k is [blk_s, blk_s + blk_n); lane l prefetches the source row of triplet blk_s + l
+    uint32_t blk_s[KW], blk_n[KW];
+    int32_t iv[KW];
+#pragma unroll
+    for (int t = 0; t < KW; ++t) {
+        cn[t] = (wave + NW * t) < K ? cn[t] - st[t] : 0u;
+        blk_s[t] = __builtin_amdgcn_readlane(st[t], 0);
+        blk_n[t] = (wave + NW * t) < K ? __builtin_amdgcn_readlane(st[t] + cn[t], 31) - blk_s[t] : 0u;
+        const uint32_t p = blk_s[t] + lane;
+        iv[t] = gather[p < last_triplet ? p : last_triplet];
+    }
+#pragma unroll
+    for (int t = 0; t < KW; ++t) asm volatile("" : "+v"(iv[t]));   // keep these loads ahead of the cell loop
+
+    v16f acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[b][j] = 0.f;
+
+#pragma unroll
+    for (int t = 0; t < KW; ++t) {
+        const int k = wave + NW * t;
+        const uint32_t n = blk_n[t];
+        if (n == 0) continue;                        // wave-uniform: no triplet of the block in cell k
+        v4u bw[NB][NPC];
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int pc = 0; pc < NPC; ++pc) bw[b][pc] = wfrag[(((size_t)k * NB + b) * NPC + pc) * 64];
+
+        // ---- stage 1: sums of the runs, 16 triplets per step -------------------------------------
+        v16f d1[NS1];
+#pragma unroll
+        for (int s = 0; s < NS1; ++s)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) d1[s][j] = 0.f;
+        const int rel = (int)(st[t] - blk_s[t]);     // this centre's run, relative to the block's run
+        const int cnr = (int)cn[t];
+        int32_t ivc = iv[t];
+        for (uint32_t p0 = 0; p0 < n; p0 += 16) {
+            if (p0 != 0 && (p0 & 63) == 0) {         // next 64 source rows
+                const uint32_t p = blk_s[t] + p0 + lane;
+                ivc = gather[p < last_triplet ? p : last_triplet];
+            }
+            // lane (c, h) reads dword column c (+32 g) of triplets p0 + 8 h + e
+            uint32_t xv[8][NG];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t tt = p0 + 8 * h + e;
+                const uint32_t src = (uint32_t)__shfl(ivc, (int)(tt & 63), 64);
+                const uint32_t off = tt < n ? src * ROWB + (uint32_t)c * 4 : OOB_OFFSET;
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    xv[e][g] = __builtin_amdgcn_raw_buffer_load_b32(frs, (int)(off + g * 128), 0, 0);
+            }
+            // selection operand: lane (centre c, h), element e = 1.0 when triplet p0 + 8 h + e is in the centre's run
+            v4u sel;
+            {
+                const int lo = rel - (int)(p0 + 8 * h);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool in0 = (uint32_t)(2 * q - lo) < (uint32_t)cnr;
+                    const bool in1 = (uint32_t)(2 * q + 1 - lo) < (uint32_t)cnr;
+                    sel[q] = (in0 ? 0x3f80u : 0u) | (in1 ? 0x3f800000u : 0u);
+                }
+            }
+            const v8bf selv = __builtin_bit_cast(v8bf, sel);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if constexpr (BF16) {
+                    v4u ev, od;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        ev[q] = __builtin_amdgcn_perm(xv[2 * q + 1][g], xv[2 * q][g], 0x05040100u);
+                        od[q] = __builtin_amdgcn_perm(xv[2 * q + 1][g], xv[2 * q][g], 0x07060302u);
+                    }
+                    d1[2 * g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ev), selv, d1[2 * g], 0, 0, 0);
+                    d1[2 * g + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, od), selv, d1[2 * g + 1], 0, 0, 0);
+                } else {
+                    // x = x1 + x2 + x3 exactly, each term a bf16 (8 significant bits)
+                    v4u p1, p2, p3;
+                    uint32_t a1[8], a2[8], a3[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float x = __uint_as_float(xv[e][g]);
+                        a1[e] = xv[e][g] & 0xffff0000u;
+                        const float r1 = x - __uint_as_float(a1[e]);
+                        a2[e] = __float_as_uint(r1) & 0xffff0000u;
+                        a3[e] = __float_as_uint(r1 - __uint_as_float(a2[e]));
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        p1[q] = __builtin_amdgcn_perm(a1[2 * q + 1], a1[2 * q], 0x07060302u);
+                        p2[q] = __builtin_amdgcn_perm(a2[2 * q + 1], a2[2 * q], 0x07060302u);
+                        p3[q] = __builtin_amdgcn_perm(a3[2 * q + 1], a3[2 * q], 0x07060302u);
+                    }
+                    d1[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, p1), selv, d1[g], 0, 0, 0);
+                    d1[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, p2), selv, d1[g], 0, 0, 0);
+                    d1[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, p3), selv, d1[g], 0, 0, 0);
+                }
+            }
+        }
+
+        // ---- stage 2: acc += S_k . W[k]^T; d1[s][j] of lane (centre, h) is channel column 8 (j/4) + 4 h + j%4 ----
+        if constexpr (BF16) {
+#pragma unroll
+            for (int s = 0; s < NS1; ++s)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    v4u a;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) a[q] = cvt_pk_bf16(d1[s][8 * s2 + 2 * q], d1[s][8 * s2 + 2 * q + 1]);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a),
+                                                                         __builtin_bit_cast(v8bf, bw[b][s * 2 + s2]),
+                                                                         acc[b], 0, 0, 0);
+                }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(d1[g][j], __uint_as_float(bw[b][g * 4 + j / 4][j % 4]),
+                                                                      acc[b], 0, 0, 0);
+        }
+    }
+
+    // add the waves' accumulators in wave order, wave 0 writes the rows
+    if (wave > 0) {
+        float *mine = red + (size_t)(wave - 1) * NB * 16 * 64;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mine[(b * 16 + j) * 64 + lane] = acc[b][j];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            float v = acc[b][j];
+#pragma unroll
+            for (int wv = 0; wv < NW - 1; ++wv) v += red[((size_t)wv * NB * 16 + b * 16 + j) * 64 + lane];
+            const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
+            if (row < n_centres) {
+                if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + b * 32 + c] = v;
+                else dst[(size_t)row * C_DST + b * 32 + c] = (uint16_t)(cvt_pk_bf16(v, 0.f) & 0xffffu);
+            }
+        }
+}
+
+template <bool BF16, int C_SRC, int C_DST, int KW, int NW>
+int launch(const MvmrArgs &a, hipStream_t stream)
+{
+    const int64_t blocks = ceil_div(a.n_centres, ROWS);
+    const size_t lds = (size_t)(NW - 1) * (C_DST / 32) * 16 * 64 * sizeof(float);
+    const uint32_t last = (uint32_t)(a.n_triplets - 1);
+    const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * (BF16 ? 2 : 4));
+    if (a.out_dtype == PCPP_F32) {
+        rows_kernel<BF16, C_SRC, C_DST, KW, NW, float><<<(unsigned)blocks, NW * 64, lds, stream>>>(
+            a.feat, a.w, static_cast<float *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+    } else {
+        rows_kernel<BF16, C_SRC, C_DST, KW, NW, uint16_t><<<(unsigned)blocks, NW * 64, lds, stream>>>(
+            a.feat, a.w, static_cast<uint16_t *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
+    }
+    PCPP_HIP_CHECK(hipGetLastError());
+    return PCPP_OK;
+}
+
+// four waves per block; 2 cells per wave cover K <= 8, 7 cover K <= 28
+template <bool BF16, int C_SRC, int C_DST>
+int launch_k(const MvmrArgs &a, hipStream_t stream)
+{
+    if (a.K <= 8) return launch<BF16, C_SRC, C_DST, 2, 4>(a, stream);
+    return launch<BF16, C_SRC, C_DST, 7, 4>(a, stream);
+}
+
+}  // namespace
+
+bool mvmr_rows_sel_supported(const MvmrArgs &a)
+{
+    if (a.n_triplets <= 0 || a.K > 28) return false;
+    const size_t es = a.in_dtype == PCPP_BF16 ? 2 : 4;
+    if ((size_t)a.n_src * a.c_src * es > MAX_BUFFER_BYTES) return false;
+    if (a.in_dtype == PCPP_F32 && a.out_dtype == PCPP_F32)
+        return (a.c_src == 32 && a.c_dst == 32) || (a.c_src == 64 && a.c_dst == 64);
+    if (a.in_dtype == PCPP_BF16)
+        return (a.c_src == 64 && a.c_dst == 64) || (a.c_src == 64 && a.c_dst == 128) || (a.c_src == 128 && a.c_dst == 64);
+    return false;
+}
+
+int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s,
+                         int dtype, hipStream_t stream)
+{
+    const int e = dtype == PCPP_BF16 ? 8 : 4;
+    const int64_t total = (int64_t)K * (c_dst / 32) * (c_src / e / 2) * 64;
+    const unsigned blocks = (unsigned)ceil_div(total, 256);
+    if (dtype == PCPP_BF16)
+        pack_w_sel_kernel<uint16_t><<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w),
+                                                                static_cast<uint16_t *>(packed), K, c_src, c_dst,
+                                                                stride_d, stride_s);
+    else
+        pack_w_sel_kernel<float><<<blocks, 256, 0, stream>>>(static_cast<const float *>(w),
+                                                             static_cast<float *>(packed), K, c_src, c_dst, stride_d,
+                                                             stride_s);
+    PCPP_HIP_CHECK(hipGetLastError());
+    return PCPP_OK;
+}
+
+// a.w must be the weights packed by mvmr_rows_sel_pack_w
+int mvmr_rows_sel(const MvmrArgs &a, hipStream_t stream)
+{
+    if (a.in_dtype == PCPP_F32) {
+        if (a.c_src == 32 && a.c_dst == 32) return launch_k<false, 32, 32>(a, stream);
+        if (a.c_src == 64 && a.c_dst == 64) return launch_k<false, 64, 64>(a, stream);
+    } else {
+        if (a.c_src == 64 && a.c_dst == 64) return launch_k<true, 64, 64>(a, stream);
+        if (a.c_src == 64 && a.c_dst == 128) return launch_k<true, 64, 128>(a, stream);
+        if (a.c_src == 128 && a.c_dst == 64) return launch_k<true, 128, 64>(a, stream);
+    }
+    set_error("mvmr_rows_sel: unsupported shape");
+    return PCPP_ERR_UNSUPPORTED;
+}
+
+}  // namespace pcpp

@@ -88,6 +88,11 @@ struct MvmrArgs {
 };
 
 int mvmr_rows_generic(const MvmrArgs &a, hipStream_t stream);              // fwd and bwd_input
+// rows kernel with both the run sums and the W product on the matrix cores (mvmr_rows.hip), K <= 28
+bool mvmr_rows_sel_supported(const MvmrArgs &a);
+int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s,
+                         int dtype, hipStream_t stream);
+int mvmr_rows_sel(const MvmrArgs &a, hipStream_t stream);   // a.w = weights packed by mvmr_rows_sel_pack_w
 bool mvmr_rows_mfma_supported(const MvmrArgs &a);
 int mvmr_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s, int dtype,
                 hipStream_t stream);

@@ -156,7 +156,7 @@ def test_dense_cluster_uses_rescan_path(pcpp):
     try:
         T = build_gpu(pcpp, p, p, 0.05, 3, same=True)
     finally:
-        assert L.pcpp_debug_set_list_cap(2048) == 0
+        assert L.pcpp_debug_set_list_cap(512) == 0
     assert np.bincount(o).max() > 40
     check_triplets(T, o, i, k, seg)
 
