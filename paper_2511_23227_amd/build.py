@@ -19,7 +19,7 @@ SOURCES = {
     "scan.hip": [],
     "build_triplets.hip": ["-ffp-contract=off"],
     "mvmr_generic.hip": [],
-    "mvmr_mfma.hip": [],
+    "mvmr_weight.hip": [],
     "mvmr_rows.hip": [],
 }
 

@@ -1,0 +1,273 @@
+// Weight gradient (VVOR), Eq. (5) of Sec. 3.3.3, on the matrix cores: dW[k] = sum over cell k's run of
+// dy[o] (x) x[i].  The (k, o, i) ordered triplet list is cut into equal chunks, one per wave (per
+// sub-block of dW for wide layers); the reduction index of the MFMA is the triplet, both operands are
+// rows read straight from memory (lane <-> channel), chunk partial sums go to the workspace and are
+// added in a fixed order by a second kernel: no atomics, reproducible.
+#include <stdlib.h>
+
+#include "pcpp_internal.h"
+
+namespace pcpp {
+
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+constexpr int WAVES = 4;
+
+
+// MFMA register layouts used below (wave64):
+//   v_mfma_f32_32x32x2_f32 :  A: lane (m = l%32, h = l/32) gives A[m][h];  B: lane (n, h) gives B[h][n]
+//   v_mfma_f32_32x32x16_bf16: A: lane (m, h) gives A[m][8h .. 8h+7];       B: lane (n, h) gives B[8h .. 8h+7][n]
+//   D (both): lane l, register j -> row 8*(j/4) + 4*(l/32) + j%4, column l%32.
+
+// ---------------------------------------------------------------------------------------------
+// Weight gradient (VVOR), Eq. (5).  Wave c owns triplets [c*chunk, (c+1)*chunk) of the (k, o, i)
+// ordered list.  A chunk usually lies inside one cell's run; where a run starts inside the chunk the
+// accumulator is flushed and restarted.  Slots of the partial buffer:
+//   slot c               sum for the cell of the chunk's first triplet
+//   slot n_chunks + k    sum for cell k over the part of its run that starts inside a chunk
+// fp32: one MFMA step consumes 2 triplets: lane (c, h) supplies channel c of dy[o] and of x[i] of
+// triplet 2 s + h.  bf16: one step consumes 16 triplets; a lane reads one dword (2 channels) per
+// triplet and the even / odd channels form separate 32-wide blocks of the operand.
+// ---------------------------------------------------------------------------------------------
+// Wide layers: a wave owns a SUB_OUT x SUB_IN block of dW[k]; the n_sub waves that share a chunk are
+// consecutive, so their re-reads of the same rows are served by the L1 / L2 caches.
+template <bool BF16, int C_IN, int C_OUT, int SUB_IN, int SUB_OUT>
+__global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
+                                                            float *__restrict__ part,
+                                                            const int32_t *__restrict__ tri_o,
+                                                            const int32_t *__restrict__ tri_i,
+                                                            const int64_t *__restrict__ seg, int K, int64_t n_triplets,
+                                                            int chunk, int64_t n_chunks)
+{
+    constexpr int NBI = SUB_IN / 32, NBO = SUB_OUT / 32;
+    constexpr int N_SUB_IN = C_IN / SUB_IN, N_SUB = N_SUB_IN * (C_OUT / SUB_OUT);
+    constexpr int STEP = BF16 ? 16 : 2;      // triplets per MFMA step
+    constexpr int NS = 32 / STEP;            // steps per batch of 32 triplets
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
+    const int64_t chunk_id = gw / N_SUB;
+    const int sub = (int)(gw % N_SUB);
+    const int ci0 = (sub % N_SUB_IN) * SUB_IN, co0 = (sub / N_SUB_IN) * SUB_OUT;
+    if (chunk_id >= n_chunks) return;
+    int64_t p = chunk_id * chunk;
+    int64_t p_end = p + chunk;
+    if (p_end > n_triplets) p_end = n_triplets;
+
+    // cell of the first triplet: the k with seg[k] <= p < seg[k+1]
+    int k = 0;
+    for (int kb = 0; kb < K; kb += 64) {
+        const int kk = kb + lane;
+        const bool hit = kk < K && seg[kk] <= p && p < seg[kk + 1];
+        const unsigned long long msk = __ballot(hit);
+        if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
+    }
+
+    v16f acc[NBO][NBI];
+    bool first = true;
+    while (p < p_end) {
+        int64_t q = seg[k + 1];
+        if (q > p_end) q = p_end;
+        if (q <= p) { ++k; continue; }       // empty run
+#pragma unroll
+        for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+            for (int bi = 0; bi < NBI; ++bi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[bo][bi][j] = 0.f;
+
+        for (int64_t b0 = p; b0 < q; b0 += 32) {
+            const int n = (int)(q - b0 < 32 ? q - b0 : 32);
+            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
+            int32_t oi = 0;
+            if (c < n) oi = h == 0 ? tri_o[b0 + c] : tri_i[b0 + c];
+            if constexpr (!BF16) {
+                float a[NBO][NS], b[NBI][NS];
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const int t = 2 * s + h;
+                    const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
+                    const float *dyr = static_cast<const float *>(dy_) + (size_t)o * C_OUT + co0 + c;
+                    const float *xr = static_cast<const float *>(x_) + (size_t)i * C_IN + ci0 + c;
+#pragma unroll
+                    for (int bo = 0; bo < NBO; ++bo) a[bo][s] = t < n ? dyr[bo * 32] : 0.f;
+#pragma unroll
+                    for (int bi = 0; bi < NBI; ++bi) b[bi][s] = t < n ? xr[bi * 32] : 0.f;
+                }
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+                        for (int bi = 0; bi < NBI; ++bi)
+                            acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bo][s], b[bi][s], acc[bo][bi], 0, 0, 0);
+            } else {
+                // block index of the operand = 2 * q + parity: channel 2 * (c + 32 q) + parity
+                constexpr int QO = SUB_OUT / 64, QI = SUB_IN / 64;
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    uint32_t dyw[QO][8], xw[QI][8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int t = 16 * s + 8 * h + e;
+                        const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
+                        const uint32_t *dyr = static_cast<const uint32_t *>(dy_) + (size_t)o * (C_OUT / 2) + co0 / 2 + c;
+                        const uint32_t *xr = static_cast<const uint32_t *>(x_) + (size_t)i * (C_IN / 2) + ci0 / 2 + c;
+#pragma unroll
+                        for (int qo = 0; qo < QO; ++qo) dyw[qo][e] = t < n ? dyr[qo * 32] : 0u;
+#pragma unroll
+                        for (int qi = 0; qi < QI; ++qi) xw[qi][e] = t < n ? xr[qi * 32] : 0u;
+                    }
+                    v4u av[NBO], bv[NBI];
+#pragma unroll
+                    for (int qo = 0; qo < QO; ++qo)
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; ++e2) {
+                            av[2 * qo][e2] = (dyw[qo][2 * e2] & 0xffffu) | (dyw[qo][2 * e2 + 1] << 16);
+                            av[2 * qo + 1][e2] = (dyw[qo][2 * e2] >> 16) | (dyw[qo][2 * e2 + 1] & 0xffff0000u);
+                        }
+#pragma unroll
+                    for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; ++e2) {
+                            bv[2 * qi][e2] = (xw[qi][2 * e2] & 0xffffu) | (xw[qi][2 * e2 + 1] << 16);
+                            bv[2 * qi + 1][e2] = (xw[qi][2 * e2] >> 16) | (xw[qi][2 * e2 + 1] & 0xffff0000u);
+                        }
+#pragma unroll
+                    for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+                        for (int bi = 0; bi < NBI; ++bi)
+                            acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av[bo]),
+                                                                                  __builtin_bit_cast(v8bf, bv[bi]),
+                                                                                  acc[bo][bi], 0, 0, 0);
+                }
+            }
+        }
+        // flush
+        float *dstp = part + (size_t)(first ? chunk_id : n_chunks + k) * C_OUT * C_IN;
+#pragma unroll
+        for (int bo = 0; bo < NBO; ++bo)
+#pragma unroll
+            for (int bi = 0; bi < NBI; ++bi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int r = 8 * (j / 4) + 4 * h + (j % 4);
+                    int co, ci;
+                    if constexpr (BF16) {
+                        co = co0 + 2 * (r + 32 * (bo >> 1)) + (bo & 1);
+                        ci = ci0 + 2 * (c + 32 * (bi >> 1)) + (bi & 1);
+                    } else {
+                        co = co0 + bo * 32 + r;
+                        ci = ci0 + bi * 32 + c;
+                    }
+                    dstp[(size_t)co * C_IN + ci] = acc[bo][bi][j];
+                }
+        first = false;
+        p = q;
+        ++k;
+    }
+}
+
+// dw[k][e] = (partial of the run's head, if it starts inside a chunk) + partials of the chunks whose first
+// triplet lies in run k.  16 threads share one element: thread g adds chunks c0+g, c0+g+16, ... in
+// ascending order and the 16 sums are then added in order of g, so the result is reproducible.
+// grid = (ceil(c_out*c_in / 16), K), block = 256
+__global__ __launch_bounds__(256) void weight_reduce(const float *__restrict__ part, float *__restrict__ dw,
+                                                     const int64_t *__restrict__ seg, int n_elem, int chunk,
+                                                     int64_t n_chunks)
+{
+    __shared__ float sums[16][17];
+    const int el = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const int e = blockIdx.x * 16 + el;
+    const int k = blockIdx.y;
+    const int64_t s = seg[k], t = seg[k + 1];
+    float v = 0.f;
+    if (t > s && e < n_elem) {
+        const int64_t c0 = (s + chunk - 1) / chunk, c1 = (t + chunk - 1) / chunk;
+        for (int64_t c = c0 + g; c < c1; c += 16) v += part[(size_t)c * n_elem + e];
+    }
+    sums[g][el] = v;
+    __syncthreads();
+    if (g == 0 && e < n_elem) {
+        float r = (t > s && s % chunk != 0) ? part[(size_t)(n_chunks + k) * n_elem + e] : 0.f;
+#pragma unroll
+        for (int gg = 0; gg < 16; ++gg) r += sums[gg][el];
+        dw[(size_t)k * n_elem + e] = r;
+    }
+}
+
+// triplets per chunk: at least 512, grown so that there are at most about 8192 chunks (2048 for wide
+// layers, whose partial sums are large)
+int weight_chunk(int64_t n_triplets, int c_in, int c_out)
+{
+    const int64_t max_chunks = (int64_t)c_in * c_out >= 128 * 128 ? 2048 : 8192;
+    int chunk = 512;
+    while ((n_triplets + chunk - 1) / chunk > max_chunks) chunk *= 2;
+    return chunk;
+}
+
+template <bool BF16, int C_IN, int C_OUT, int SUB_IN = C_IN, int SUB_OUT = C_OUT>
+int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int64_t *seg, void *workspace,
+                  size_t workspace_bytes, hipStream_t stream)
+{
+    const int n_elem = C_IN * C_OUT;
+    const int chunk = weight_chunk(a.n_triplets, C_IN, C_OUT);
+    const int64_t n_chunks = ceil_div(a.n_triplets, chunk);
+    constexpr int N_SUB = (C_IN / SUB_IN) * (C_OUT / SUB_OUT);
+    const size_t need = (size_t)(n_chunks + a.K) * n_elem * sizeof(float);
+    if (workspace_bytes < need) {
+        set_error("pcpp_mvmr_bwd_weight: workspace has %zu bytes, needs %zu", workspace_bytes, need);
+        return PCPP_ERR_WORKSPACE;
+    }
+    float *part = static_cast<float *>(workspace);
+    if (n_chunks > 0) {
+        weight_kernel<BF16, C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
+            a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
+    dim3 grid((unsigned)ceil_div(n_elem, 16), (unsigned)a.K);
+    weight_reduce<<<grid, 256, 0, stream>>>(part, dw, seg, n_elem, chunk, n_chunks);
+    PCPP_HIP_CHECK(hipGetLastError());
+    return PCPP_OK;
+}
+
+bool weight_shape_supported(int in_dtype, int c_in, int c_out)
+{
+    if (in_dtype == PCPP_F32) return (c_in == 32 && c_out == 32) || (c_in == 64 && c_out == 64);
+    return (c_in == 64 && c_out == 64) || (c_in == 64 && c_out == 128) || (c_in == 128 && c_out == 128) ||
+           (c_in == 256 && c_out == 256);
+}
+
+}  // namespace
+
+// c_src = c_in (x), c_dst = c_out (dy, passed as `dense`); gather = tri_i
+int mvmr_weight_mfma(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int64_t *seg, void *workspace,
+                     size_t workspace_bytes, hipStream_t stream, bool *handled)
+{
+    *handled = true;
+    if (a.in_dtype == PCPP_F32) {
+        if (a.c_src == 32 && a.c_dst == 32) return launch_weight<false, 32, 32>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 64 && a.c_dst == 64) return launch_weight<false, 64, 64>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+    } else {
+        if (a.c_src == 64 && a.c_dst == 64) return launch_weight<true, 64, 64>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 64 && a.c_dst == 128) return launch_weight<true, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 128 && a.c_dst == 128) return launch_weight<true, 128, 128, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+        if (a.c_src == 256 && a.c_dst == 256) return launch_weight<true, 256, 256, 64, 128>(a, dw, tri_o, seg, workspace, workspace_bytes, stream);
+    }
+    *handled = false;
+    return PCPP_OK;
+}
+
+size_t mvmr_weight_mfma_workspace_bytes(int64_t n_triplets, int c_in, int c_out, int K, int in_dtype)
+{
+    if (!weight_shape_supported(in_dtype, c_in, c_out)) return 0;
+    const int chunk = weight_chunk(n_triplets, c_in, c_out);
+    return align_up((size_t)(ceil_div(n_triplets, chunk) + K) * c_in * c_out * sizeof(float));
+}
+
+}  // namespace pcpp

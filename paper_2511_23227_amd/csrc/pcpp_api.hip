@@ -2,7 +2,6 @@
 // (pcpp_build_triplets lives in build_triplets.hip.)
 #include <stdarg.h>
 #include <stdio.h>
-#include <stdlib.h>
 
 #include "pcpp_internal.h"
 
@@ -132,22 +131,15 @@ int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out
     a.in_dtype = in_dtype; a.out_dtype = out_dtype;
     a.n_src = n_in; a.n_centres = n_out; a.c_src = c_in; a.c_dst = c_out; a.K = K;
     a.gather = tri_i; a.side = side_view(plan, pl.fwd); a.n_triplets = n_triplets;
-    const bool sel = mvmr_rows_sel_supported(a) && !getenv("PCPP_NO_SEL");
-    if (sel || mvmr_rows_mfma_supported(a)) {
+    if (mvmr_rows_sel_supported(a)) {
         const size_t need = pcpp_mvmr_workspace_bytes(0, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
         if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
             set_error("pcpp_mvmr_fwd: workspace missing, misaligned or smaller than %zu bytes", need);
             return PCPP_ERR_WORKSPACE;
         }
-        if (sel) {
-            if ((rc = mvmr_rows_sel_pack_w(w, workspace, K, c_in, c_out, c_in, 1, in_dtype, stream)) != PCPP_OK) return rc;
-            a.w = workspace;
-            return mvmr_rows_sel(a, stream);
-        }
-        if ((rc = mvmr_pack_w(w, workspace, K, c_in, c_out, c_in, 1, in_dtype, stream)) != PCPP_OK) return rc;
+        if ((rc = mvmr_rows_sel_pack_w(w, workspace, K, c_in, c_out, c_in, 1, in_dtype, stream)) != PCPP_OK) return rc;
         a.w = workspace;
-        bool handled = false;
-        return mvmr_rows_mfma(a, stream, &handled);
+        return mvmr_rows_sel(a, stream);
     }
     return mvmr_rows_generic(a, stream);
 }
@@ -176,14 +168,9 @@ int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, i
     a.n_src = n_out; a.n_centres = n_in; a.c_src = c_out; a.c_dst = c_in; a.K = K;
     a.side = side_view(plan, pl.bwd); a.gather = a.side.gather; a.n_triplets = n_triplets;
     // W[k] is [c_out][c_in]; the rows kernel wants (dst = c_in, src = c_out) = W[k]^T
-    if (mvmr_rows_sel_supported(a) && !getenv("PCPP_NO_SEL")) {
+    if (mvmr_rows_sel_supported(a)) {
         if ((rc = mvmr_rows_sel_pack_w(w, workspace, K, c_out, c_in, 1, c_in, in_dtype, stream)) != PCPP_OK) return rc;
         return mvmr_rows_sel(a, stream);
-    }
-    if (mvmr_rows_mfma_supported(a)) {
-        if ((rc = mvmr_pack_w(w, workspace, K, c_out, c_in, 1, c_in, in_dtype, stream)) != PCPP_OK) return rc;
-        bool handled = false;
-        return mvmr_rows_mfma(a, stream, &handled);
     }
     if ((rc = transpose_w(w, workspace, K, c_out, c_in, in_dtype, stream)) != PCPP_OK) return rc;
     return mvmr_rows_generic(a, stream);

@@ -72,7 +72,7 @@ int scan_exclusive_u32(const uint32_t *in, uint32_t *out, int64_t n, void *scrat
 int fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t stream);
 int fill_u64(unsigned long long *p, unsigned long long v, int64_t n, hipStream_t stream);
 
-// ---- MVMR kernels (mvmr_generic.hip, mvmr_mfma.hip) -----------------------------------------
+// ---- MVMR kernels (mvmr_generic.hip, mvmr_rows.hip, mvmr_weight.hip) -------------------------
 struct MvmrArgs {
     const void *feat;        // gathered tensor: x (fwd, bwd_weight) or dy (bwd_input), [n_src, c_src]
     const void *w;           // fwd: W [K][c_dst][c_src];  bwd_input: W^T [K][c_dst][c_src] (already transposed)
@@ -88,15 +88,11 @@ struct MvmrArgs {
 };
 
 int mvmr_rows_generic(const MvmrArgs &a, hipStream_t stream);              // fwd and bwd_input
-// rows kernel with both the run sums and the W product on the matrix cores (mvmr_rows.hip), K <= 28
+// rows kernels with both the run sums and the W product on the matrix cores (mvmr_rows.hip)
 bool mvmr_rows_sel_supported(const MvmrArgs &a);
 int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s,
                          int dtype, hipStream_t stream);
 int mvmr_rows_sel(const MvmrArgs &a, hipStream_t stream);   // a.w = weights packed by mvmr_rows_sel_pack_w
-bool mvmr_rows_mfma_supported(const MvmrArgs &a);
-int mvmr_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s, int dtype,
-                hipStream_t stream);
-int mvmr_rows_mfma(const MvmrArgs &a, hipStream_t stream, bool *handled);  // tuned shapes; a.w = packed weights
 int transpose_w(const void *w, void *wt, int K, int c_out, int c_in, int dtype, hipStream_t stream);
 int mvmr_weight_generic(const MvmrArgs &a, float *dw, void *workspace, size_t workspace_bytes,
                         hipStream_t stream);
