@@ -146,6 +146,30 @@ def main() -> int:
     per_op = {op: roofline(op) for op in ops}
     dominant = max(ops, key=lambda o_: op_ms[o_])
 
+    # Matrix-core work actually issued by the rows kernels (fwd / bwd_input): one 32 x C_src x C_dst product per
+    # (cell, 32-centre block) that holds a triplet, plus the run sums (one 32 x 32 x 16 selection product per 16
+    # triplets and 32 source channels; three per 16 triplets for fp32 inputs).  Blocks without a triplet are skipped.
+    def executed_flops(centre, c_src, c_dst):
+        key = T.tri_k.long() * ((int(centre.max()) >> 5) + 1) + (centre.long() >> 5)
+        _, cnt = torch.unique(key, return_counts=True)
+        steps = ((cnt + 15) // 16).sum().item()
+        terms = 1 if s.dtype == "bf16" else 3
+        return cnt.numel() * 2.0 * 32 * c_src * c_dst + steps * terms * 2.0 * 16 * 32 * c_src
+    if n_t > 0:
+        ex = {"fwd": executed_flops(T.tri_o, s.c_in, s.c_out)}
+        if "bwd_input" in ops:
+            ex["bwd_input"] = executed_flops(T.tri_i, s.c_out, s.c_in)
+        if "bwd_weight" in ops:
+            ex["bwd_weight"] = 2.0 * n_t * s.c_in * s.c_out      # one outer product per triplet, nothing skipped
+        peak = MFMA_PEAK_TFLOPS[s.dtype]
+        for op in ops:
+            tf = ex[op] / (op_ms[op] * 1e-3) / 1e12
+            per_op[op]["executed_mfma_tflops"] = round(tf, 2)
+            per_op[op]["mfma_frac"] = round(tf / peak, 4)
+            if s.dtype == "bf16" and min(s.c_in, s.c_out) >= 256:   # wide layers are matrix-core bound
+                per_op[op].update({"bound": "mfma", "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s",
+                                   "frac": round(tf / peak, 4)})
+
     result = {
         "metric": "MVMR fwd+bwd neighbour-pairs/s (whole hot path: triplet build + fwd + bwd_input + bwd_weight)",
         "value": round(n_t / (ms_per_step * 1e-3), 1),
@@ -166,7 +190,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         # bounded sample of the same workload: the first n_sample outputs against all inputs
-        n_sample = min(s.n_out, max(1024, int(2.0e9 / max(s.n_in, 1))))
+        n_sample = min(s.n_out, max(1024, int(2.0e10 / max(s.n_in, 1))))   # about 10-30 s of host work
         sub = np.ascontiguousarray(s.out_xyz[:n_sample])
         c0 = time.perf_counter()
         o, i, k, seg = oracle.build_triplets(s.in_xyz, sub, s.radius, s.t)
