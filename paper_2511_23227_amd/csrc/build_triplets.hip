@@ -19,6 +19,7 @@ constexpr int CELL_BIAS = 1 << 20;
 constexpr double CELL_CLAMP = (double)((1 << 20) - 2);   // +-1 stencil steps stay inside 21 bits
 constexpr int SEARCH_THREADS = 1024;                      // 16 waves share a tile of 64 centres: 4 centres each
 constexpr int SEARCH_WAVES = SEARCH_THREADS / 64;
+constexpr int COUNT_ILP = 4;                              // centres a wave of the count pass handles at once
 constexpr int LIST_CAP_MAX = 512;                         // neighbours of one centre kept in LDS (per wave)
 
 __device__ inline uint32_t hash_key(unsigned long long k)
@@ -194,14 +195,25 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__res
     const int64_t tile = blockIdx.x;
     for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
     __syncthreads();
-    for (int al = wave; al < TILE; al += SEARCH_WAVES) {
-        const int64_t a = tile * TILE + al;
-        if (a >= n_centres) break;             // wave-uniform
-        Candidates<SWAP> c;
-        c.open(centres, a, g, lane);
-        for (uint32_t base = 0; base < c.total; base += 64) {
-            int b, k;
-            if (c.fetch(base + lane, g, q, b, k)) atomicAdd(&tbl[k * TILE + al], 1u);
+    // each wave works on COUNT_ILP centres at once so that their dependent loads overlap
+    for (int al0 = wave; al0 < TILE; al0 += SEARCH_WAVES * COUNT_ILP) {
+        Candidates<SWAP> c[COUNT_ILP];
+        uint32_t most = 0;
+#pragma unroll
+        for (int u = 0; u < COUNT_ILP; ++u) {
+            const int al = al0 + u * SEARCH_WAVES;
+            const int64_t a = tile * TILE + al;
+            const bool ok = al < TILE && a < n_centres;            // wave-uniform
+            c[u].open(centres, ok ? a : 0, g, lane);
+            if (!ok) c[u].total = 0;
+            most = c[u].total > most ? c[u].total : most;
+        }
+        for (uint32_t base = 0; base < most; base += 64) {
+#pragma unroll
+            for (int u = 0; u < COUNT_ILP; ++u) {
+                int b, k;
+                if (c[u].fetch(base + lane, g, q, b, k)) atomicAdd(&tbl[k * TILE + al0 + u * SEARCH_WAVES], 1u);
+            }
         }
     }
     __syncthreads();
