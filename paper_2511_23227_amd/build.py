@@ -21,6 +21,8 @@ SOURCES = {
     "mvmr_generic.hip": [],
     "mvmr_weight.hip": [],
     "mvmr_rows.hip": [],
+    # MFMA results in ordinary vector registers unless register pressure moves them (see the file header)
+    "mvmr_rows_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -23,32 +23,11 @@
 // v_mfma_f32_32x32x2_f32: A: lane (M, h) holds A[M][h]; B: lane (N, h) holds B[h][N]; D as above.
 #include <stdlib.h>
 
-#include "pcpp_internal.h"
+#include "mvmr_rows_common.h"
 
 namespace pcpp {
 
 namespace {
-
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef float v2f __attribute__((ext_vector_type(2)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-
-constexpr int ROWS = 32;                         // centres per block
-constexpr uint32_t OOB_OFFSET = 0xffffff00u;     // buffer offset past any descriptor: reads zero, no traffic
-constexpr size_t MAX_BUFFER_BYTES = 0xfffff000u;
-
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
-}
-
-__device__ inline uint32_t cvt_pk_bf16(float lo, float hi)
-{
-    const v2f v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf));   // round to nearest even
-}
 
 // Source channel of element e of packed piece pc for lane-half h (see the header comment and rows_kernel).
 //   fp32: piece pc = g*4 + v      : 4 floats, channel 32 g + 8 v + 4 h + e
@@ -311,302 +290,6 @@ __global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ 
         }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Wide layers (bf16, C_SRC a multiple of 64 with at least 3 chunks, any K): W[k] is too large to be
-// re-read per 32 centres, so a block of eight waves owns 256 consecutive centres (32 per wave) and
-// shares W through LDS.  The work is a sequence of steps (active cell k, 64-channel chunk c of the
-// source row).  Per step every wave runs stage 1 on the matching 128-byte slice of its triplets'
-// source rows and stage 2 against the 64 x C_DST slice of W[k] held in one of two LDS buffers.
-// Everything a step needs was requested one step earlier: the W slice (global -> registers -> LDS),
-// the first 32 triplets' row slices, and -- spread over a cell's chunks -- the run bounds and gather
-// indices of the next active cell.  One barrier per step; cells without a triplet among the block's
-// 256 centres are skipped by the whole block.
-//   packed W: piece (((k*NCH + c)*NB + b)*4 + v)*64 + lane = W(k, b*32 + lane%32, packed_channel(c*4 + v, lane/32, e))
-// ---------------------------------------------------------------------------------------------
-constexpr int WIDE_WAVES = 8;
-
-__global__ void pack_w_wide_kernel(const uint16_t *__restrict__ w, uint16_t *__restrict__ packed, int K, int c_src,
-                                   int c_dst, int stride_d, int stride_s)
-{
-    const int nch = c_src / 64, nb = c_dst / 32;
-    const int64_t total = (int64_t)K * nch * nb * 4 * 64;
-    const int64_t piece = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (piece >= total) return;
-    const int lane = (int)(piece & 63);
-    int64_t r = piece >> 6;
-    const int v = (int)(r & 3); r >>= 2;
-    const int b = (int)(r % nb); r /= nb;
-    const int c = (int)(r % nch);
-    const int k = (int)(r / nch);
-    const int d = b * 32 + (lane & 31);
-    const uint16_t *src = w + (size_t)k * c_dst * c_src + (size_t)d * stride_d;
-    uint16_t *dstp = packed + piece * 8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) dstp[e] = src[(size_t)packed_channel<true>(c * 4 + v, lane >> 5, e) * stride_s];
-}
-
-template <int C_SRC, int C_DST, typename TOut>
-__global__ __launch_bounds__(WIDE_WAVES * 64) void rows_wide_kernel(const void *__restrict__ feat_,
-                                                                    const void *__restrict__ w_, TOut *__restrict__ dst,
-                                                                    int64_t n_centres, int K,
-                                                                    const int32_t *__restrict__ gather,
-                                                                    uint32_t last_triplet, uint32_t feat_bytes,
-                                                                    PlanSideView side)
-{
-    constexpr uint32_t ROWB = C_SRC * 2;
-    constexpr int NCH = C_SRC / 64;                  // source chunks of 32 dwords
-    constexpr int NB = C_DST / 32;                   // destination blocks
-    constexpr int PIECES = NB * 4 * 64;              // 16-byte pieces of one W slice
-    constexpr int PPT = PIECES / (WIDE_WAVES * 64);  // pieces copied per thread
-    static_assert(NCH >= 3 && PPT >= 1, "shape not supported by the wide kernel");
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    v4u *wbuf = reinterpret_cast<v4u *>(lds);                    // [2][PIECES]
-    v4u *sel_tab = wbuf + 2 * PIECES;                            // [256]
-    int *act = reinterpret_cast<int *>(sel_tab + 256);           // [256] active cells, [256] = their number
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 31, h = lane >> 5;
-    const int64_t blk = (int64_t)blockIdx.x * WIDE_WAVES + wave;  // 32-centre block of this wave
-    const int64_t row0 = blk * ROWS;
-    const bool valid = row0 < n_centres;                          // wave-uniform
-    int64_t tile = blk >> 1;
-    if (tile >= side.n_tiles) tile = side.n_tiles - 1;
-    const int sub = (int)(blk & 1) * ROWS;
-    const bool last_in_tile = (sub + c) == TILE - 1;
-    const __amdgpu_buffer_rsrc_t frs = make_rsrc(feat_, feat_bytes);
-    const v4u *wsrc = static_cast<const v4u *>(w_) + threadIdx.x;
-    const uint32_t *runs = side.run_start + (size_t)tile * K * TILE + sub + c;
-    const uint32_t *tends = side.tile_ptr + tile + 1;
-    const int64_t t0 = (int64_t)blockIdx.x * (WIDE_WAVES / 2);
-    const int64_t t1 = t0 + WIDE_WAVES / 2 < side.n_tiles ? t0 + WIDE_WAVES / 2 : side.n_tiles;
-
-    for (int b = threadIdx.x; b < 256; b += WIDE_WAVES * 64) {
-        v4u v;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            v[q] = (((b >> (2 * q)) & 1) ? 0x3f80u : 0u) | (((b >> (2 * q + 1)) & 1) ? 0x3f800000u : 0u);
-        sel_tab[b] = v;
-    }
-    if (wave == 0) {                                              // cells with a triplet among the 256 centres
-        int cnt = 0;
-        for (int kb = 0; kb < K; kb += 64) {
-            const int k = kb + lane;
-            const bool a = k < K && side.tile_ptr[(size_t)k * side.n_tiles + t0] != side.tile_ptr[(size_t)k * side.n_tiles + t1];
-            const unsigned long long m = __ballot(a);
-            if (a) act[cnt + __popcll(m & ((1ull << lane) - 1ull))] = k;
-            cnt += __popcll(m);
-        }
-        if (lane == 0) act[256] = cnt;
-    }
-    __syncthreads();
-    const int n_act = act[256];
-    const int total_steps = n_act * NCH;
-
-    auto load_runs = [&](int k, uint32_t &st, uint32_t &en) {
-        const uint32_t *pe = last_in_tile ? tends + (size_t)k * side.n_tiles : runs + (size_t)k * TILE + 1;
-        st = runs[(size_t)k * TILE];
-        en = *pe;
-    };
-    auto row_offsets = [&](int32_t iv, uint32_t n) -> uint32_t {   // byte offset of triplet `lane`'s source row
-        return (uint32_t)lane < n ? (uint32_t)iv * ROWB : OOB_OFFSET;
-    };
-
-    v16f acc[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[b][j] = 0.f;
-
-    if (total_steps > 0) {
-        // first active cell, unpipelined
-        uint32_t st_c, en_c;
-        load_runs(act[0], st_c, en_c);
-        uint32_t bs_c = __builtin_amdgcn_readlane(st_c, 0);
-        uint32_t n_c = valid ? __builtin_amdgcn_readlane(en_c, 31) - bs_c : 0u;
-        uint32_t cn_c = valid ? en_c - st_c : 0u;
-        uint32_t offv_c;
-        {
-            const uint32_t p = bs_c + lane;
-            offv_c = row_offsets(gather[p < last_triplet ? p : last_triplet], n_c);
-        }
-        uint32_t st_n = 0, en_n = 0, bs_n = 0, n_n = 0;
-        int32_t iv_n = 0;
-        // W slice of step 0 and the first 32 triplets' row slices of step 0
-        v4u wr[PPT];
-#pragma unroll
-        for (int q = 0; q < PPT; ++q) wr[q] = wsrc[(size_t)act[0] * NCH * PIECES + q * WIDE_WAVES * 64];
-        uint32_t xa[2][8];
-#pragma unroll
-        for (int p = 0; p < 2; ++p)
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                xa[p][e] = __builtin_amdgcn_raw_buffer_load_b32(
-                    frs, (int)((uint32_t)__shfl((int)offv_c, 16 * p + 8 * h + e, 64) + (uint32_t)c * 4), 0, 0);
-
-        for (int s = 0; s < total_steps; ++s) {
-            const int j = s / NCH, ch = s % NCH;
-            const int k = act[j];
-            v4u *buf = wbuf + (size_t)(s & 1) * PIECES;
-            // (1) this step's W slice into LDS, next step's slice requested
-#pragma unroll
-            for (int q = 0; q < PPT; ++q) buf[threadIdx.x + q * WIDE_WAVES * 64] = wr[q];
-            if (s + 1 < total_steps) {
-                const size_t nxt = ((size_t)act[(s + 1) / NCH] * NCH + (s + 1) % NCH) * PIECES;
-#pragma unroll
-                for (int q = 0; q < PPT; ++q) wr[q] = wsrc[nxt + q * WIDE_WAVES * 64];
-            }
-            // (2) next active cell: run bounds at chunk 0, gather indices at chunk 1, used from the last chunk on
-            const bool more = j + 1 < n_act;
-            if (ch == 0 && more) load_runs(act[j + 1], st_n, en_n);
-            if (ch == 1 && more) {
-                bs_n = __builtin_amdgcn_readlane(st_n, 0);
-                n_n = valid ? __builtin_amdgcn_readlane(en_n, 31) - bs_n : 0u;
-                const uint32_t p = bs_n + lane;
-                iv_n = gather[p < last_triplet ? p : last_triplet];
-            }
-            uint32_t offv_n = OOB_OFFSET;
-            if (ch == NCH - 1 && more) offv_n = row_offsets(iv_n, n_n);
-            // (3) triplets 32..63 of this step (not prefetched) and the first 32 of the next step
-            const uint32_t slice = (uint32_t)ch * 128 + (uint32_t)c * 4;
-            uint32_t xe[2][8];
-            if (n_c > 32) {
-#pragma unroll
-                for (int p = 0; p < 2; ++p)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        xe[p][e] = __builtin_amdgcn_raw_buffer_load_b32(
-                            frs, (int)((uint32_t)__shfl((int)offv_c, 32 + 16 * p + 8 * h + e, 64) + slice), 0, 0);
-            }
-            uint32_t xb[2][8];
-            {
-                const uint32_t offv = ch == NCH - 1 ? offv_n : offv_c;
-                const uint32_t nslice = (uint32_t)((ch + 1) % NCH) * 128 + (uint32_t)c * 4;
-#pragma unroll
-                for (int p = 0; p < 2; ++p)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        xb[p][e] = __builtin_amdgcn_raw_buffer_load_b32(
-                            frs, (int)((uint32_t)__shfl((int)offv, 16 * p + 8 * h + e, 64) + nslice), 0, 0);
-            }
-            // (4) stage 1: sums of the runs for this 64-channel slice
-            v16f d1[2];
-#pragma unroll
-            for (int par = 0; par < 2; ++par)
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) d1[par][jj] = 0.f;
-            if (n_c != 0) {
-                const int rel = (int)(st_c - bs_c);
-                auto run_window = [&](uint32_t g0) -> unsigned long long {
-                    int lo = rel - (int)g0, hi = lo + (int)cn_c;
-                    lo = lo < 0 ? 0 : (lo > 64 ? 64 : lo);
-                    hi = hi < 0 ? 0 : (hi > 64 ? 64 : hi);
-                    return (hi >= 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~(lo >= 64 ? ~0ull : ((1ull << lo) - 1ull));
-                };
-                auto sel_step = [&](const uint32_t (&x)[8], unsigned long long bits, int p) {
-                    const v8bf selv = __builtin_bit_cast(v8bf, sel_tab[(uint32_t)(bits >> (16 * p + 8 * h)) & 0xffu]);
-                    v4u ev, od;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        ev[q] = __builtin_amdgcn_perm(x[2 * q + 1], x[2 * q], 0x05040100u);
-                        od[q] = __builtin_amdgcn_perm(x[2 * q + 1], x[2 * q], 0x07060302u);
-                    }
-                    d1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ev), selv, d1[0], 0, 0, 0);
-                    d1[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, od), selv, d1[1], 0, 0, 0);
-                };
-                const unsigned long long bits0 = run_window(0);
-                sel_step(xa[0], bits0, 0);
-                if (n_c > 16) sel_step(xa[1], bits0, 1);
-                if (n_c > 32) sel_step(xe[0], bits0, 2);
-                if (n_c > 48) sel_step(xe[1], bits0, 3);
-                for (uint32_t g0 = 64; g0 < n_c; g0 += 64) {     // rare: more than 64 triplets of the block in one cell
-                    const uint32_t p = bs_c + g0 + lane;
-                    const uint32_t offv = g0 + lane < n_c ? (uint32_t)gather[p < last_triplet ? p : last_triplet] * ROWB
-                                                          : OOB_OFFSET;
-                    const unsigned long long bits = run_window(g0);
-#pragma unroll
-                    for (int p4 = 0; p4 < 4; ++p4) {
-                        if (g0 + 16 * p4 < n_c) {
-                            uint32_t x[8];
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                x[e] = __builtin_amdgcn_raw_buffer_load_b32(
-                                    frs, (int)((uint32_t)__shfl((int)offv, 16 * p4 + 8 * h + e, 64) + slice), 0, 0);
-                            sel_step(x, bits, p4);
-                        }
-                    }
-                }
-            }
-            v4u a[4];
-#pragma unroll
-            for (int par = 0; par < 2; ++par)
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        a[par * 2 + s2][q] = cvt_pk_bf16(d1[par][8 * s2 + 2 * q], d1[par][8 * s2 + 2 * q + 1]);
-            __syncthreads();                                      // the W slice is complete in LDS
-            // (5) stage 2 against the shared slice
-            if (n_c != 0) {
-                const v4u *bl = buf + lane;
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[v]),
-                                                                         __builtin_bit_cast(v8bf, bl[(b * 4 + v) * 64]),
-                                                                         acc[b], 0, 0, 0);
-            }
-            // (6) rotate
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xa[p][e] = xb[p][e];
-            if (ch == NCH - 1 && more) {
-                st_c = st_n; en_c = en_n; bs_c = bs_n; n_c = n_n;
-                cn_c = valid ? en_c - st_c : 0u;
-                offv_c = offv_n;
-            }
-            (void)k;
-        }
-    }
-    if (!valid) return;
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
-            if (row < n_centres) {
-                if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + b * 32 + c] = acc[b][j];
-                else dst[(size_t)row * C_DST + b * 32 + c] = (uint16_t)(cvt_pk_bf16(acc[b][j], 0.f) & 0xffffu);
-            }
-        }
-}
-
-template <int C_SRC, int C_DST>
-int launch_wide(const MvmrArgs &a, hipStream_t stream)
-{
-    const int64_t blocks = ceil_div(ceil_div(a.n_centres, ROWS), WIDE_WAVES);
-    const size_t lds = (size_t)2 * (C_DST / 32) * 4 * 64 * 16 + 256 * 16 + 257 * sizeof(int);
-    const uint32_t last = (uint32_t)(a.n_triplets - 1);
-    const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * 2);
-    if (a.out_dtype == PCPP_F32) {
-        auto kern = rows_wide_kernel<C_SRC, C_DST, float>;
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        kern<<<(unsigned)blocks, WIDE_WAVES * 64, lds, stream>>>(a.feat, a.w, static_cast<float *>(a.dst), a.n_centres,
-                                                                 a.K, a.gather, last, feat_bytes, a.side);
-    } else {
-        auto kern = rows_wide_kernel<C_SRC, C_DST, uint16_t>;
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        kern<<<(unsigned)blocks, WIDE_WAVES * 64, lds, stream>>>(a.feat, a.w, static_cast<uint16_t *>(a.dst),
-                                                                 a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
-    }
-    PCPP_HIP_CHECK(hipGetLastError());
-    return PCPP_OK;
-}
-
-bool wide_shape(const MvmrArgs &a) { return a.in_dtype == PCPP_BF16 && a.c_src == 256 && a.c_dst == 256; }
-
 template <bool BF16, int C_SRC, int C_DST, int NW>
 int launch(const MvmrArgs &a, hipStream_t stream)
 {
@@ -642,7 +325,7 @@ bool mvmr_rows_sel_supported(const MvmrArgs &a)
     if (a.n_triplets <= 0) return false;
     const size_t es = a.in_dtype == PCPP_BF16 ? 2 : 4;
     if ((size_t)a.n_src * a.c_src * es > MAX_BUFFER_BYTES) return false;
-    if (wide_shape(a)) return true;
+    if (mvmr_rows_wide_shape(a)) return true;
     if (a.K > 64) return false;                      // narrow layers with many cells: generic path
     if (a.in_dtype == PCPP_F32 && a.out_dtype == PCPP_F32)
         return (a.c_src == 32 && a.c_dst == 32) || (a.c_src == 64 && a.c_dst == 64);
@@ -657,12 +340,8 @@ int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_ds
     const int e = dtype == PCPP_BF16 ? 8 : 4;
     const int64_t total = (int64_t)K * (c_dst / 32) * (c_src / e / 2) * 64;
     const unsigned blocks = (unsigned)ceil_div(total, 256);
-    if (dtype == PCPP_BF16 && c_src == 256 && c_dst == 256) {
-        pack_w_wide_kernel<<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w), static_cast<uint16_t *>(packed),
-                                                       K, c_src, c_dst, stride_d, stride_s);
-        PCPP_HIP_CHECK(hipGetLastError());
-        return PCPP_OK;
-    }
+    if (dtype == PCPP_BF16 && c_src == 256 && c_dst == 256)
+        return mvmr_rows_wide_pack_w(w, packed, K, c_src, c_dst, stride_d, stride_s, stream);
     if (dtype == PCPP_BF16)
         pack_w_sel_kernel<uint16_t><<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w),
                                                                 static_cast<uint16_t *>(packed), K, c_src, c_dst,
@@ -678,7 +357,7 @@ int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_ds
 // a.w must be the weights packed by mvmr_rows_sel_pack_w
 int mvmr_rows_sel(const MvmrArgs &a, hipStream_t stream)
 {
-    if (wide_shape(a)) return launch_wide<256, 256>(a, stream);
+    if (mvmr_rows_wide_shape(a)) return mvmr_rows_wide(a, stream);
     if (a.in_dtype == PCPP_F32) {
         if (a.c_src == 32 && a.c_dst == 32) return launch_k<false, 32, 32>(a, stream);
         if (a.c_src == 64 && a.c_dst == 64) return launch_k<false, 64, 64>(a, stream);
