@@ -268,7 +268,17 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
     }
     uint32_t *list = list_all[wave];
     const unsigned long long lane_lt = (1ull << lane) - 1ull;
-    for (int al = wave; al < TILE; al += SEARCH_WAVES) {
+    // the wave's centres are opened together so that their dependent grid loads overlap
+    constexpr int PER_WAVE = TILE / SEARCH_WAVES;
+    Candidates<SWAP> cand[PER_WAVE];
+#pragma unroll
+    for (int u = 0; u < PER_WAVE; ++u) {
+        const int64_t a = tile * TILE + wave + u * SEARCH_WAVES;
+        cand[u].open(centres, a < n_centres ? a : 0, g, lane);
+    }
+#pragma unroll
+    for (int u = 0; u < PER_WAVE; ++u) {
+        const int al = wave + u * SEARCH_WAVES;
         const int64_t a = tile * TILE + al;
         if (a >= n_centres) break;             // wave-uniform
         // bucket of cell k = [bbase, bbase + bcnt) in the list; lane (k % 64) of group (k / 64) holds it
@@ -286,8 +296,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
             }
         }
         if (n == 0) continue;                  // wave-uniform
-        Candidates<SWAP> c;
-        c.open(centres, a, g, lane);
+        const Candidates<SWAP> &c = cand[u];
         if (n <= SMALL_LIST && n <= (uint32_t)list_cap) {
             // few neighbours: one flat list of (cell, index) keys in arrival order, rank by comparing all pairs
             unsigned long long *keys = reinterpret_cast<unsigned long long *>(list);
