@@ -69,6 +69,38 @@ __global__ void pack_w_sel_kernel(const T *__restrict__ w, T *__restrict__ packe
     for (int e = 0; e < E; ++e) dst[e] = src[(size_t)packed_channel<BF16>(pc, lane >> 5, e) * stride_s];
 }
 
+// fp32 layers whose stage 2 runs on the bf16 matrix cores: W is stored as three bf16 terms, W = w1 + w2 + w3
+// exactly (8 + 8 + 8 significant bits).  Piece (k*NB + b)*(3*KS) + kap*3 + t, lane (dst = b*32 + lane%32,
+// h = lane/32), element e = term t of W(k, dst, channel 8 (2 kap + e/4) + 4 h + e%4).
+constexpr bool split_f32_shape(bool bf16, int c_src, int c_dst) { return !bf16 && c_src == 32 && c_dst == 32; }
+
+__global__ void pack_w_split_kernel(const float *__restrict__ w, uint16_t *__restrict__ packed, int K, int c_src,
+                                    int c_dst, int stride_d, int stride_s)
+{
+    const int nb = c_dst / 32, ks = c_src / 16;      // reduction steps of 16 channels
+    const int64_t total = (int64_t)K * nb * ks * 3 * 64;
+    const int64_t piece = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (piece >= total) return;
+    const int lane = (int)(piece & 63);
+    int64_t r = piece >> 6;
+    const int t = (int)(r % 3); r /= 3;
+    const int kap = (int)(r % ks); r /= ks;
+    const int b = (int)(r % nb);
+    const int k = (int)(r / nb);
+    const int d = b * 32 + (lane & 31), h = lane >> 5;
+    const float *src = w + (size_t)k * c_dst * c_src + (size_t)d * stride_d;
+    uint16_t *dstp = packed + piece * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = src[(size_t)(8 * (2 * kap + (e >> 2)) + 4 * h + (e & 3)) * stride_s];
+        const uint32_t a1 = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(a1);
+        const uint32_t a2 = __float_as_uint(r1) & 0xffff0000u;
+        const uint32_t a3 = __float_as_uint(r1 - __uint_as_float(a2));
+        dstp[e] = (uint16_t)((t == 0 ? a1 : (t == 1 ? a2 : a3)) >> 16);
+    }
+}
+
 template <bool BF16, int C_SRC, int C_DST, int NW, typename TOut>
 __global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
                                                        TOut *__restrict__ dst, int64_t n_centres, int K,
@@ -80,7 +112,8 @@ __global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ 
     constexpr int NP = BF16 ? 2 : 1;                 // even / odd channel of a dword (bf16)
     constexpr int NS1 = NG * NP;                     // stage-1 accumulator blocks of 32 channels
     constexpr int NB = C_DST / 32;                   // destination blocks
-    constexpr int NPC = BF16 ? NS1 * 2 : NG * 4;     // packed W pieces per (cell, destination block)
+    constexpr bool SPLIT = split_f32_shape(BF16, C_SRC, C_DST);   // fp32 stage 2 as products of bf16 terms
+    constexpr int NPC = BF16 ? NS1 * 2 : (SPLIT ? 3 * (C_SRC / 16) : NG * 4);   // packed W pieces per (cell, destination block)
     constexpr uint32_t ROWB = DW * 4;
     constexpr int RED_FLOATS = (NW - 1) * NB * 16 * 64;
     extern __shared__ __attribute__((aligned(16))) float smem[];   // [RED_FLOATS] reduction + [256] selection table (v4u)
@@ -247,6 +280,42 @@ __global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ 
                             acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                                 __builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, bw[b][s * 2 + s2]), acc[b], 0, 0, 0);
                     }
+            } else if constexpr (SPLIT) {
+                // S = s1 + s2 + s3 and W = w1 + w2 + w3 exactly, each term a bf16; the six products of weight
+                // 2^-16 or more relative to s1 w1 are accumulated in fp32, smallest first.  Registers 8 kap ..
+                // 8 kap + 7 of lane (centre, h) are the channels 8 (2 kap + e/4) + 4 h + e%4 of reduction step kap.
+                static_assert(NG == 1, "split stage 2 is written for 32 source channels");
+                uint32_t t1[16], t2[16], t3[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float x = d1[0][j];
+                    t1[j] = __float_as_uint(x) & 0xffff0000u;
+                    const float r1 = x - __uint_as_float(t1[j]);
+                    t2[j] = __float_as_uint(r1) & 0xffff0000u;
+                    t3[j] = __float_as_uint(r1 - __uint_as_float(t2[j]));
+                }
+#pragma unroll
+                for (int kap = 0; kap < 2; ++kap) {
+                    v4u a1, a2, a3;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        a1[q] = __builtin_amdgcn_perm(t1[8 * kap + 2 * q + 1], t1[8 * kap + 2 * q], 0x07060302u);
+                        a2[q] = __builtin_amdgcn_perm(t2[8 * kap + 2 * q + 1], t2[8 * kap + 2 * q], 0x07060302u);
+                        a3[q] = __builtin_amdgcn_perm(t3[8 * kap + 2 * q + 1], t3[8 * kap + 2 * q], 0x07060302u);
+                    }
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const v8bf w1 = __builtin_bit_cast(v8bf, bw[b][kap * 3 + 0]);
+                        const v8bf w2 = __builtin_bit_cast(v8bf, bw[b][kap * 3 + 1]);
+                        const v8bf w3 = __builtin_bit_cast(v8bf, bw[b][kap * 3 + 2]);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a3), w1, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a1), w3, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a2), w2, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a2), w1, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a1), w2, acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a1), w1, acc[b], 0, 0, 0);
+                    }
+                }
             } else {
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
@@ -342,6 +411,13 @@ int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_ds
     const unsigned blocks = (unsigned)ceil_div(total, 256);
     if (dtype == PCPP_BF16 && c_src == 256 && c_dst == 256)
         return mvmr_rows_wide_pack_w(w, packed, K, c_src, c_dst, stride_d, stride_s, stream);
+    if (split_f32_shape(dtype == PCPP_BF16, c_src, c_dst)) {
+        const int64_t pieces = (int64_t)K * (c_dst / 32) * (c_src / 16) * 3 * 64;
+        pack_w_split_kernel<<<(unsigned)ceil_div(pieces, 256), 256, 0, stream>>>(
+            static_cast<const float *>(w), static_cast<uint16_t *>(packed), K, c_src, c_dst, stride_d, stride_s);
+        PCPP_HIP_CHECK(hipGetLastError());
+        return PCPP_OK;
+    }
     if (dtype == PCPP_BF16)
         pack_w_sel_kernel<uint16_t><<<blocks, 256, 0, stream>>>(static_cast<const uint16_t *>(w),
                                                                 static_cast<uint16_t *>(packed), K, c_src, c_dst,

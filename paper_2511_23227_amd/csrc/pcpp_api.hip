@@ -102,7 +102,7 @@ size_t pcpp_mvmr_workspace_bytes(int op, int64_t n_in, int64_t n_out, int64_t n_
     if (n_in < 0 || n_out < 0 || n_triplets < 0 || c_in < 1 || c_out < 1 || K < 1) return 0;
     switch (op) {
     case 0:                                                                     // W in fragment order
-    case 1: return align_up((size_t)K * c_out * c_in * elem_size(in_dtype));   // W^T, plain or in fragment order
+    case 1: return align_up((size_t)K * c_out * c_in * (in_dtype == PCPP_F32 ? 6 : 2));   // W / W^T in fragment order (fp32: up to three bf16 terms)
     case 2: {                                                                   // partial dW per range of centres
         const size_t g = mvmr_weight_workspace_bytes(n_out, c_in, c_out, K);
         const size_t m = mvmr_weight_mfma_workspace_bytes(n_triplets, c_in, c_out, K, in_dtype);
