@@ -86,7 +86,7 @@ def main() -> int:
                    tri_k=torch.empty(n_t, dtype=torch.int32, device="cuda"),
                    seg_offsets=torch.empty(s.K + 1, dtype=torch.int64, device="cuda"),
                    plan=torch.empty(L.pcpp_plan_bytes(s.n_in, s.n_out, s.t, n_t, flags), dtype=torch.uint8, device="cuda"),
-                   workspace=torch.empty(L.pcpp_build_triplets_workspace_bytes(s.n_in, s.n_out, s.t),
+                   workspace=torch.empty(L.pcpp_build_triplets_workspace_bytes_for(s.n_in, s.n_out, s.t, n_t),
                                          dtype=torch.uint8, device="cuda"))
     ws = {i_: torch.empty(max(256, L.pcpp_mvmr_workspace_bytes(i_, s.n_in, s.n_out, n_t, s.c_in, s.c_out, s.K, code)),
                           dtype=torch.uint8, device="cuda") for i_ in range(3)}

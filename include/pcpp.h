@@ -68,13 +68,17 @@ int pcpp_version(void);
  *                        triplets regrouped by (k, i, o) for the input gradient
  *                        (PCPP_PLAN_BWD_INPUT).  plan_flags selects the parts; NULL => none.
  *   workspace            scratch of pcpp_build_triplets_workspace_bytes(...) bytes, 256-byte
- *                        aligned; contents are undefined afterwards.
+ *                        aligned; contents are undefined afterwards.  With at least
+ *                        pcpp_build_triplets_workspace_bytes_for(..., capacity) bytes the neighbours
+ *                        found while counting are kept and the second pass does not search again
+ *                        (same results, about a third less time).
  * in_xyz [n_in,3] and out_xyz [n_out,3] may alias (outputs at the inputs).
  * Errors: INVALID_ARG (null xyz with n > 0, radius not finite or <= 0, t outside 1..PCPP_MAX_T,
  * some but not all tri_* NULL), CAPACITY, WORKSPACE, UNSUPPORTED (|T| >= 2^31), HIP.
  * Non-finite coordinates are not supported (undefined triplets, no fault).
  * ------------------------------------------------------------------------------------------- */
 size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t);
+size_t pcpp_build_triplets_workspace_bytes_for(int64_t n_in, int64_t n_out, int t, int64_t capacity);
 size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags);
 
 int pcpp_build_triplets(const float *in_xyz, int64_t n_in,

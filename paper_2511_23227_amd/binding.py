@@ -14,7 +14,8 @@ PCPP_F32, PCPP_BF16 = 0, 1
 PLAN_FWD, PLAN_BWD_INPUT = 1, 2
 ERR_CAPACITY = -2
 
-EXPORTS = ("pcpp_last_error", "pcpp_version", "pcpp_build_triplets_workspace_bytes", "pcpp_plan_bytes",
+EXPORTS = ("pcpp_last_error", "pcpp_version", "pcpp_build_triplets_workspace_bytes",
+           "pcpp_build_triplets_workspace_bytes_for", "pcpp_plan_bytes",
            "pcpp_build_triplets", "pcpp_mvmr_workspace_bytes", "pcpp_mvmr_fwd", "pcpp_mvmr_bwd_input",
            "pcpp_mvmr_bwd_weight")
 
@@ -43,6 +44,8 @@ def library() -> ctypes.CDLL:
     L.pcpp_version.restype = i32
     L.pcpp_build_triplets_workspace_bytes.restype = sz
     L.pcpp_build_triplets_workspace_bytes.argtypes = [i64, i64, i32]
+    L.pcpp_build_triplets_workspace_bytes_for.restype = sz
+    L.pcpp_build_triplets_workspace_bytes_for.argtypes = [i64, i64, i32, i64]
     L.pcpp_plan_bytes.restype = sz
     L.pcpp_plan_bytes.argtypes = [i64, i64, i32, i64, i32]
     L.pcpp_build_triplets.restype = i32
@@ -140,11 +143,15 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
     if ws_bytes == 0:
         raise PcppError(-1, "invalid sizes or t")
     ws = buffers.get("workspace")
-    if ws is None or ws.numel() < ws_bytes:
-        ws = _bytes(ws_bytes, dev)
     if capacity is None:
+        if ws is None or ws.numel() < ws_bytes:
+            ws = _bytes(ws_bytes, dev)
         capacity = pcpp_count_triplets(in_xyz, out_xyz, radius, t, ws)
     cap = max(int(capacity), 1)
+    # room for the neighbour lists that let the second pass skip its search
+    ws_bytes = max(ws_bytes, L.pcpp_build_triplets_workspace_bytes_for(n_in, n_out, t, cap))
+    if ws is None or ws.numel() < ws_bytes:
+        ws = _bytes(ws_bytes, dev)
 
     def buf(name, numel, dtype):
         b = buffers.get(name)

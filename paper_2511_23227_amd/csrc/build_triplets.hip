@@ -180,6 +180,9 @@ struct Candidates {
     }
 };
 
+constexpr int HIT_INDEX_BITS = 24;         // a stored hit = cell << 24 | candidate index
+constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
+
 // ---- pass 1: neighbours per (cell k, centre) --------------------------------------------------
 // One block per tile of TILE centres, one wave per centre at a time.
 //   tile_cnt   [n_tiles][K][TILE]   (may be NULL: totals only)
@@ -188,7 +191,8 @@ template <bool SWAP>
 __global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__restrict__ centres, int64_t n_centres,
                                                               GridView g, QueryParams q, int K, int64_t n_tiles,
                                                               uint32_t *__restrict__ tile_cnt,
-                                                              uint32_t *__restrict__ tile_k_cnt)
+                                                              uint32_t *__restrict__ tile_k_cnt,
+                                                              uint32_t *__restrict__ hits, uint32_t hit_stride)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -208,11 +212,22 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__res
             if (!ok) c[u].total = 0;
             most = c[u].total > most ? c[u].total : most;
         }
+        uint32_t filled[COUNT_ILP];
+#pragma unroll
+        for (int u = 0; u < COUNT_ILP; ++u) filled[u] = 0;
         for (uint32_t base = 0; base < most; base += 64) {
 #pragma unroll
             for (int u = 0; u < COUNT_ILP; ++u) {
                 int b, k;
-                if (c[u].fetch(base + lane, g, q, b, k)) atomicAdd(&tbl[k * TILE + al0 + u * SEARCH_WAVES], 1u);
+                const bool hit = c[u].fetch(base + lane, g, q, b, k);
+                if (hit) atomicAdd(&tbl[k * TILE + al0 + u * SEARCH_WAVES], 1u);
+                if (hits) {                        // the centre's first hit_stride neighbours, in arrival order
+                    const unsigned long long m = __ballot(hit);
+                    const uint32_t slot = filled[u] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                    if (hit && slot < hit_stride)
+                        hits[(size_t)(tile * TILE + al0 + u * SEARCH_WAVES) * hit_stride + slot] = ((uint32_t)k << HIT_INDEX_BITS) | (uint32_t)b;
+                    filled[u] += (uint32_t)__popcll(m);
+                }
             }
         }
     }
@@ -247,7 +262,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
                                                              const uint32_t *__restrict__ tile_ptr,
                                                              int32_t *__restrict__ out_c, int32_t *__restrict__ out_b,
                                                              int32_t *__restrict__ out_k,
-                                                             uint32_t *__restrict__ run_start_out, int list_cap)
+                                                             uint32_t *__restrict__ run_start_out, int list_cap,
+                                                             const uint32_t *__restrict__ hits, uint32_t hit_stride)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
     __shared__ uint32_t list_all[SEARCH_WAVES][LIST_CAP_MAX];
@@ -268,19 +284,59 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
     }
     uint32_t *list = list_all[wave];
     const unsigned long long lane_lt = (1ull << lane) - 1ull;
-    // the wave's centres are opened together so that their dependent grid loads overlap
+    // A centre whose neighbours the count pass left in `hits` needs no second search.  The others are opened
+    // together so that their dependent grid loads overlap.
     constexpr int PER_WAVE = TILE / SEARCH_WAVES;
+    const uint32_t reuse_max = hits ? (hit_stride < SMALL_LIST ? hit_stride : SMALL_LIST) : 0u;
     Candidates<SWAP> cand[PER_WAVE];
+    uint32_t n_of[PER_WAVE];
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
-        const int64_t a = tile * TILE + wave + u * SEARCH_WAVES;
-        cand[u].open(centres, a < n_centres ? a : 0, g, lane);
+        const int al = wave + u * SEARCH_WAVES;
+        const int64_t a = tile * TILE + al;
+        uint32_t nn = 0;
+        if (a < n_centres)
+            for (int k = lane; k < K; k += 64) nn += cnt_tile[k * TILE + al];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) nn += __shfl_xor(nn, d, 64);
+        n_of[u] = nn;
+        if (nn > reuse_max || nn > (uint32_t)list_cap) cand[u].open(centres, a, g, lane);   // wave-uniform
     }
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
         const int al = wave + u * SEARCH_WAVES;
         const int64_t a = tile * TILE + al;
         if (a >= n_centres) break;             // wave-uniform
+        if (n_of[u] == 0) continue;            // wave-uniform
+        if (n_of[u] <= reuse_max && n_of[u] <= (uint32_t)list_cap) {
+            // rank the stored (cell, index) keys by comparing all pairs
+            const uint32_t n = n_of[u];
+            const uint32_t *mine = hits + (size_t)a * hit_stride;
+            for (uint32_t e = lane; e < n; e += 64) list[e] = mine[e];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (uint32_t e = lane; e < n; e += 64) {
+                const uint32_t key = list[e];
+                const uint32_t kbase = key & ~HIT_INDEX_MASK, rel = key & HIT_INDEX_MASK;
+                uint32_t rank = 0, e2 = 0;
+                for (; e2 + 8 <= n; e2 += 8) {
+                    uint32_t v[8];
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) v[w] = list[e2 + w];
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) rank += (v[w] - kbase) < rel ? 1u : 0u;
+                }
+                for (; e2 < n; ++e2) rank += (list[e2] - kbase) < rel ? 1u : 0u;
+                const int k = (int)(key >> HIT_INDEX_BITS);
+                const uint32_t pos = tbl[k * TILE + al] + rank;
+                if (out_c) out_c[pos] = (int32_t)a;
+                if (out_b) out_b[pos] = (int32_t)rel;
+                if (out_k) out_k[pos] = k;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            continue;
+        }
         // bucket of cell k = [bbase, bbase + bcnt) in the list; lane (k % 64) of group (k / 64) holds it
         uint32_t bcnt[KGROUPS], bbase[KGROUPS], bcur[KGROUPS];
         uint32_t n = 0;
@@ -447,10 +503,24 @@ struct BuildScratch {
     size_t total_off;                // unsigned long long[2]
     size_t fwd_ptr_off, fwd_cnt_off; // used when the caller gives no plan
     size_t bwd_ptr_off, bwd_cnt_off;
-    size_t end;
+    size_t end;                      // without hit lists
+    // Optional, after `end`: the first hit_stride neighbours of every centre as found by the count pass, so
+    // that the fill pass need not search again (needs the triplet capacity to size the lists).
+    uint32_t fwd_stride = 0, bwd_stride = 0;
+    size_t fwd_hits_off = 0, bwd_hits_off = 0, end_with_hits = 0;
 };
 
-BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K)
+// list length per centre: twice the mean neighbour count, within [32, SMALL_LIST]
+uint32_t hit_stride_for(int64_t capacity, int64_t n_centres)
+{
+    if (n_centres <= 0 || capacity <= 0) return 0;
+    int64_t s = (2 * ceil_div(capacity, n_centres) + 15) / 16 * 16;
+    if (s < 32) s = 32;
+    if (s > (int64_t)SMALL_LIST) s = SMALL_LIST;
+    return (uint32_t)s;
+}
+
+BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity = -1)
 {
     BuildScratch b;
     b.grid_in = grid_scratch(0, n_in);
@@ -467,6 +537,15 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K)
     b.bwd_ptr_off = off; off += align_up((size_t)(K * nt_i + 1) * 4);
     b.bwd_cnt_off = off; off += align_up((size_t)(nt_i > 0 ? nt_i : 1) * K * TILE * 4);
     b.end = off;
+    b.end_with_hits = off;
+    // stored hits carry the candidate index in HIT_INDEX_BITS bits
+    if (capacity > 0 && n_in < (1 << HIT_INDEX_BITS) && n_out < (1 << HIT_INDEX_BITS)) {
+        b.fwd_stride = hit_stride_for(capacity, n_out);
+        b.bwd_stride = hit_stride_for(capacity, n_in);
+        b.fwd_hits_off = off; off += align_up((size_t)n_out * b.fwd_stride * 4);
+        b.bwd_hits_off = off; off += align_up((size_t)n_in * b.bwd_stride * 4);
+        b.end_with_hits = off;
+    }
     return b;
 }
 
@@ -536,6 +615,12 @@ size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t)
     return build_scratch(n_in, n_out, t * t * t).end;
 }
 
+size_t pcpp_build_triplets_workspace_bytes_for(int64_t n_in, int64_t n_out, int t, int64_t capacity)
+{
+    if (n_in < 0 || n_out < 0 || t < 1 || t > PCPP_MAX_T || capacity < 0) return 0;
+    return build_scratch(n_in, n_out, t * t * t, capacity).end_with_hits;
+}
+
 size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags)
 {
     if (n_in < 0 || n_out < 0 || t < 1 || t > PCPP_MAX_T || n_triplets < 0) return 0;
@@ -590,7 +675,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         return PCPP_ERR_INVALID_ARG;
     }
     const int K = t * t * t;
-    const BuildScratch bs = build_scratch(n_in, n_out, K);
+    const BuildScratch bs = build_scratch(n_in, n_out, K, count_only ? -1 : capacity);
     if (!workspace || workspace_bytes < bs.end || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
         set_error("pcpp_build_triplets: workspace missing, misaligned or smaller than %zu bytes", bs.end);
         return PCPP_ERR_WORKSPACE;
@@ -601,6 +686,9 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     }
     *n_triplets = 0;
     char *ws = static_cast<char *>(workspace);
+    const bool keep_hits = bs.fwd_stride != 0 && workspace_bytes >= bs.end_with_hits;
+    uint32_t *f_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.fwd_hits_off) : nullptr;
+    uint32_t *b_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.bwd_hits_off) : nullptr;
     void *scan_scratch = ws + bs.scan_off;
     auto *total_dev = reinterpret_cast<unsigned long long *>(ws + bs.total_off);
 
@@ -640,7 +728,8 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     uint32_t *f_cnt = reinterpret_cast<uint32_t *>(ws + bs.fwd_cnt_off);
     if (nt_o > 0) {
         query_count<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o,
-                                                                         count_only ? nullptr : f_cnt, f_ptr);
+                                                                         count_only ? nullptr : f_cnt, f_ptr, f_hits,
+                                                                         bs.fwd_stride);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if ((rc = scan_exclusive_u32(f_ptr, f_ptr, (int64_t)K * nt_o, scan_scratch, total_dev, stream)) != PCPP_OK) return rc;
@@ -671,7 +760,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         uint32_t *f_runs = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
         query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
                                                                         f_ptr, tri_o, tri_i, tri_k, f_runs,
-                                                                        g_list_cap);
+                                                                        g_list_cap, f_hits, bs.fwd_stride);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if (nt_o > 0) {
@@ -702,7 +791,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         int32_t *b_gather = reinterpret_cast<int32_t *>(pb + pl.bwd.gather_off);
         if (nt_i > 0) {
             query_count<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
-                                                                            b_ptr);
+                                                                            b_ptr, b_hits, bs.bwd_stride);
             PCPP_HIP_CHECK(hipGetLastError());
         }
         if ((rc = scan_exclusive_u32(b_ptr, b_ptr, (int64_t)K * nt_i, scan_scratch, total_dev + 1, stream)) != PCPP_OK)
@@ -710,7 +799,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         if (nt_i > 0) {
             query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
                                                                            b_ptr, nullptr, b_gather, nullptr, b_runs,
-                                                                           g_list_cap);
+                                                                           g_list_cap, b_hits, bs.bwd_stride);
             PCPP_HIP_CHECK(hipGetLastError());
         }
     }
