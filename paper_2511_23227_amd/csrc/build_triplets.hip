@@ -19,7 +19,9 @@ constexpr int CELL_BIAS = 1 << 20;
 constexpr double CELL_CLAMP = (double)((1 << 20) - 2);   // +-1 stencil steps stay inside 21 bits
 constexpr int SEARCH_THREADS = 1024;                      // 16 waves share a tile of 64 centres: 4 centres each
 constexpr int SEARCH_WAVES = SEARCH_THREADS / 64;
-constexpr int COUNT_ILP = 4;                              // centres a wave of the count pass handles at once
+// Centres a wave of the count pass handles at once.  More would overlap their dependent grid loads, but the
+// registers that costs lower the occupancy below two blocks per CU, which measured worse on every scene.
+constexpr int COUNT_ILP = 1;
 constexpr int LIST_CAP_MAX = 512;                         // neighbours of one centre kept in LDS (per wave)
 
 __device__ inline uint32_t hash_key(unsigned long long k)
@@ -180,6 +182,7 @@ struct Candidates {
     }
 };
 
+constexpr uint32_t SMALL_LIST = 160;      // up to this many neighbours the all-pairs rank is cheaper than bucketing
 constexpr int HIT_INDEX_BITS = 24;         // a stored hit = cell << 24 | candidate index
 constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
 
@@ -188,18 +191,18 @@ constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
 //   tile_cnt   [n_tiles][K][TILE]   (may be NULL: totals only)
 //   tile_k_cnt [K * n_tiles]        k-major, input of the prefix sum
 template <bool SWAP>
-__global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__restrict__ centres, int64_t n_centres,
+__global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__restrict__ centres, int64_t n_centres,
                                                               GridView g, QueryParams q, int K, int64_t n_tiles,
                                                               uint32_t *__restrict__ tile_cnt,
                                                               uint32_t *__restrict__ tile_k_cnt,
                                                               uint32_t *__restrict__ hits, uint32_t hit_stride)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]
+    __shared__ uint32_t stage[SEARCH_WAVES * COUNT_ILP * SMALL_LIST];   // hit lists on their way to memory
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
     for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
     __syncthreads();
-    // each wave works on COUNT_ILP centres at once so that their dependent loads overlap
     for (int al0 = wave; al0 < TILE; al0 += SEARCH_WAVES * COUNT_ILP) {
         Candidates<SWAP> c[COUNT_ILP];
         uint32_t most = 0;
@@ -216,19 +219,35 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__res
 #pragma unroll
         for (int u = 0; u < COUNT_ILP; ++u) filled[u] = 0;
         for (uint32_t base = 0; base < most; base += 64) {
+            int b[COUNT_ILP], k[COUNT_ILP];
+            bool hit[COUNT_ILP];
 #pragma unroll
             for (int u = 0; u < COUNT_ILP; ++u) {
-                int b, k;
-                const bool hit = c[u].fetch(base + lane, g, q, b, k);
-                if (hit) atomicAdd(&tbl[k * TILE + al0 + u * SEARCH_WAVES], 1u);
-                if (hits) {                        // the centre's first hit_stride neighbours, in arrival order
-                    const unsigned long long m = __ballot(hit);
+                hit[u] = c[u].fetch(base + lane, g, q, b[u], k[u]);
+                if (hit[u]) atomicAdd(&tbl[k[u] * TILE + al0 + u * SEARCH_WAVES], 1u);
+            }
+            if (hits) {                            // every centre's first hit_stride neighbours, in arrival order
+#pragma unroll
+                for (int u = 0; u < COUNT_ILP; ++u) {
+                    const unsigned long long m = __ballot(hit[u]);
                     const uint32_t slot = filled[u] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-                    if (hit && slot < hit_stride)
-                        hits[(size_t)(tile * TILE + al0 + u * SEARCH_WAVES) * hit_stride + slot] = ((uint32_t)k << HIT_INDEX_BITS) | (uint32_t)b;
+                    if (hit[u] && slot < hit_stride)
+                        stage[(wave * COUNT_ILP + u) * SMALL_LIST + slot] = ((uint32_t)k[u] << HIT_INDEX_BITS) | (uint32_t)b[u];
                     filled[u] += (uint32_t)__popcll(m);
                 }
             }
+        }
+        if (hits) {                                // one contiguous write per centre
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int u = 0; u < COUNT_ILP; ++u) {
+                const uint32_t n = filled[u] < hit_stride ? filled[u] : hit_stride;
+                uint32_t *dst = hits + (size_t)(tile * TILE + al0 + u * SEARCH_WAVES) * hit_stride;
+                for (uint32_t e = lane; e < n; e += 64) dst[e] = stage[(wave * COUNT_ILP + u) * SMALL_LIST + e];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
     __syncthreads();
@@ -253,10 +272,9 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_count(const float *__res
 // each neighbour's rank inside its bucket (number of smaller candidate indices) gives its final slot,
 // so ties between equal (k, centre) are ordered by the other index without any global sort.
 constexpr int KGROUPS = (MAX_K + 63) / 64;
-constexpr uint32_t SMALL_LIST = 160;      // up to this many neighbours the all-pairs rank is cheaper than bucketing
 
 template <bool SWAP>
-__global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__restrict__ centres, int64_t n_centres,
+__global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__restrict__ centres, int64_t n_centres,
                                                              GridView g, QueryParams q, int K, int64_t n_tiles,
                                                              const uint32_t *__restrict__ tile_cnt,
                                                              const uint32_t *__restrict__ tile_ptr,
@@ -284,11 +302,10 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
     }
     uint32_t *list = list_all[wave];
     const unsigned long long lane_lt = (1ull << lane) - 1ull;
-    // A centre whose neighbours the count pass left in `hits` needs no second search.  The others are opened
-    // together so that their dependent grid loads overlap.
+    // A centre whose neighbours the count pass left in `hits` needs no second search.
     constexpr int PER_WAVE = TILE / SEARCH_WAVES;
     const uint32_t reuse_max = hits ? (hit_stride < SMALL_LIST ? hit_stride : SMALL_LIST) : 0u;
-    Candidates<SWAP> cand[PER_WAVE];
+    Candidates<SWAP> cand[1];
     uint32_t n_of[PER_WAVE];
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
@@ -300,7 +317,6 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) nn += __shfl_xor(nn, d, 64);
         n_of[u] = nn;
-        if (nn > reuse_max || nn > (uint32_t)list_cap) cand[u].open(centres, a, g, lane);   // wave-uniform
     }
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
@@ -352,7 +368,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void query_fill(const float *__rest
             }
         }
         if (n == 0) continue;                  // wave-uniform
-        const Candidates<SWAP> &c = cand[u];
+        Candidates<SWAP> &c = cand[0];
+        c.open(centres, a, g, lane);
         if (n <= SMALL_LIST && n <= (uint32_t)list_cap) {
             // few neighbours: one flat list of (cell, index) keys in arrival order, rank by comparing all pairs
             unsigned long long *keys = reinterpret_cast<unsigned long long *>(list);
