@@ -99,8 +99,16 @@ __global__ void pack_w_split_kernel(const float *__restrict__ w, uint16_t *__res
     }
 }
 
+// Waves per SIMD the register allocation must leave room for: the bf16 64 -> 64 layer is bound by memory
+// latency and sits just above a register-count step without this (the fp32 32 -> 32 layer, three registers
+// above the next step, loses more to the spills than it gains).
+constexpr int rows_min_waves(bool bf16, int c_src, int c_dst)
+{
+    return (bf16 && c_src == 64 && c_dst == 64) ? 3 : 1;
+}
+
 template <bool BF16, int C_SRC, int C_DST, int NW, typename TOut>
-__global__ __launch_bounds__(NW * 64) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
+__global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
                                                        TOut *__restrict__ dst, int64_t n_centres, int K,
                                                        const int32_t *__restrict__ gather, uint32_t last_triplet,
                                                        uint32_t feat_bytes, PlanSideView side)

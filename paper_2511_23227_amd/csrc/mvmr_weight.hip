@@ -37,7 +37,7 @@ constexpr int WAVES = 4;
 // Wide layers: a wave owns a SUB_OUT x SUB_IN block of dW[k]; the n_sub waves that share a chunk are
 // consecutive, so their re-reads of the same rows are served by the L1 / L2 caches.
 template <bool BF16, int C_IN, int C_OUT, int SUB_IN, int SUB_OUT>
-__global__ __launch_bounds__(WAVES * 64) void weight_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
+__global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 5 : 1) void weight_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
                                                             float *__restrict__ part,
                                                             const int32_t *__restrict__ tri_o,
                                                             const int32_t *__restrict__ tri_i,
