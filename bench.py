@@ -25,7 +25,14 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
 # (scene, order, op); absent entries are reported as null.
-MEASURED_TRAFFIC: dict = {}
+MEASURED_TRAFFIC: dict = {
+    (2, "default", "fwd"): int(283.9e6 + 12.8e6),         # rows_kernel: scaled FETCH_SIZE + WRITE_SIZE
+    (2, "default", "bwd_input"): int(283.9e6 + 12.8e6),
+    (2, "default", "bwd_weight"): int(419.1e6 + 33.3e6),  # weight_kernel (weight_reduce adds 39.7e6 read)
+    (5, "default", "fwd"): int(27555e6 + 1024e6),         # rows_wide_kernel
+    (5, "default", "bwd_input"): int(27555e6 + 1024e6),
+    (5, "default", "bwd_weight"): int(41891e6 + 543e6),   # weight_kernel
+}
 
 
 def algorithmic_bytes(op: str, n_t: int, n_in: int, n_out: int, c_in: int, c_out: int, K: int, s_in: int,
@@ -50,6 +57,9 @@ def main() -> int:
     ap.add_argument("--scene", type=int, default=2, help="synthetic scene id (default 2: the headline workload)")
     ap.add_argument("--order", default="default", choices=["default", "morton"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a 256 MiB device-to-device copy (the kernel of known size against which the "
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU only (the paper's operator is a one-GPU kernel); "
@@ -64,6 +74,14 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": src.numel() * 4, "copies": 4}))
+        return 0
     pcpp.library()
 
     s = scenes.make_scene(args.scene, order=args.order)
@@ -147,14 +165,20 @@ def main() -> int:
     dominant = max(ops, key=lambda o_: op_ms[o_])
 
     # Matrix-core work actually issued by the rows kernels (fwd / bwd_input): one 32 x C_src x C_dst product per
-    # (cell, 32-centre block) that holds a triplet, plus the run sums (one 32 x 32 x 16 selection product per 16
-    # triplets and 32 source channels; three per 16 triplets for fp32 inputs).  Blocks without a triplet are skipped.
+    # (cell, 32-centre block) that holds a triplet, plus the run sums (one selection product per 16 triplets --
+    # 32 in the wide kernel -- and 32 source channels; three for fp32 inputs, whose 32 -> 32 product itself runs as
+    # six bf16 products).  Blocks without a triplet are skipped.
     def executed_flops(centre, c_src, c_dst):
         key = T.tri_k.long() * ((int(centre.max()) >> 5) + 1) + (centre.long() >> 5)
         _, cnt = torch.unique(key, return_counts=True)
-        steps = ((cnt + 15) // 16).sum().item()
+        wide = s.dtype == "bf16" and c_src == 256 and c_dst == 256
+        per = 32 if wide else 16                      # triplets per selection product
+        steps = ((cnt + per - 1) // per).sum().item()
         terms = 1 if s.dtype == "bf16" else 3
-        return cnt.numel() * 2.0 * 32 * c_src * c_dst + steps * terms * 2.0 * 16 * 32 * c_src
+        stage2 = 2.0 * 32 * c_src * c_dst
+        if s.dtype == "f32" and c_src == 32 and c_dst == 32:
+            stage2 *= 6                               # six bf16 products of the three-term splits
+        return cnt.numel() * stage2 + steps * terms * 2.0 * per * 32 * c_src
     if n_t > 0:
         ex = {"fwd": executed_flops(T.tri_o, s.c_in, s.c_out)}
         if "bwd_input" in ops:
