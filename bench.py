@@ -185,8 +185,9 @@ def main() -> int:
             ex["bwd_input"] = executed_flops(T.tri_i, s.c_out, s.c_in)
         if "bwd_weight" in ops:
             ex["bwd_weight"] = 2.0 * n_t * s.c_in * s.c_out      # one outer product per triplet, nothing skipped
-        peak = MFMA_PEAK_TFLOPS[s.dtype]
+        split = s.dtype == "f32" and s.c_in == 32 and s.c_out == 32   # rows kernels issue bf16 products for this layer
         for op in ops:
+            peak = MFMA_PEAK_TFLOPS["bf16" if (split and op != "bwd_weight") else s.dtype]
             tf = ex[op] / (op_ms[op] * 1e-3) / 1e12
             per_op[op]["executed_mfma_tflops"] = round(tf, 2)
             per_op[op]["mfma_frac"] = round(tf / peak, 4)
