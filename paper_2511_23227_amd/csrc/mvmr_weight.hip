@@ -173,6 +173,125 @@ __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wide bf16 layers: the same chunking, with v_mfma_f32_16x16x32_bf16 (A: lane (M = l%16, g = l/16) holds
+// A[M][8g .. 8g+7]; B: lane (N = l%16, g) holds B[8g .. 8g+7][N]; D: lane l, register j -> M = 4g + j,
+// N = l%16).  One step consumes 32 triplets; lane (m, g) reads 8 bytes = channels 4m .. 4m+3 (+ 64 per
+// 64-channel group) of the rows of triplets 8g .. 8g+7, so one load instruction covers four rows and the
+// address units do half the work of dword reads.  Element q of those four channels of the eight triplets is
+// one MFMA operand: row / column m of operand (group, q) is channel 64 group + 4m + q.
+// ---------------------------------------------------------------------------------------------
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+
+template <int C_IN, int C_OUT, int SUB_IN, int SUB_OUT>
+__global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
+                                                                 float *__restrict__ part,
+                                                                 const int32_t *__restrict__ tri_o,
+                                                                 const int32_t *__restrict__ tri_i,
+                                                                 const int64_t *__restrict__ seg, int K,
+                                                                 int64_t n_triplets, int chunk, int64_t n_chunks)
+{
+    constexpr int QO = SUB_OUT / 64, QI = SUB_IN / 64;     // 64-channel groups of the sub-block
+    constexpr int N_SUB_IN = C_IN / SUB_IN, N_SUB = N_SUB_IN * (C_OUT / SUB_OUT);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
+    const int64_t chunk_id = gw / N_SUB;
+    const int sub = (int)(gw % N_SUB);
+    const int ci0 = (sub % N_SUB_IN) * SUB_IN, co0 = (sub / N_SUB_IN) * SUB_OUT;
+    if (chunk_id >= n_chunks) return;
+    int64_t p = chunk_id * chunk;
+    int64_t p_end = p + chunk;
+    if (p_end > n_triplets) p_end = n_triplets;
+
+    // cell of the first triplet: the k with seg[k] <= p < seg[k+1]
+    int k = 0;
+    for (int kb = 0; kb < K; kb += 64) {
+        const int kk = kb + lane;
+        const bool hit = kk < K && seg[kk] <= p && p < seg[kk + 1];
+        const unsigned long long msk = __ballot(hit);
+        if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
+    }
+
+    v4f acc[QO][4][QI][4];
+    bool first = true;
+    while (p < p_end) {
+        int64_t q_end = seg[k + 1];
+        if (q_end > p_end) q_end = p_end;
+        if (q_end <= p) { ++k; continue; }   // empty run
+#pragma unroll
+        for (int a = 0; a < QO; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int c = 0; c < QI; ++c)
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) acc[a][b][c][d] = v4f{0.f, 0.f, 0.f, 0.f};
+
+        for (int64_t b0 = p; b0 < q_end; b0 += 32) {
+            const int n = (int)(q_end - b0 < 32 ? q_end - b0 : 32);
+            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
+            int32_t oi = 0;
+            if ((lane & 31) < n) oi = lane < 32 ? tri_o[b0 + lane] : tri_i[b0 + lane - 32];
+            v2u dyw[QO][8], xw[QI][8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int t = 8 * g + e;
+                const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
+                const v2u *dyr = reinterpret_cast<const v2u *>(static_cast<const uint16_t *>(dy_) + (size_t)o * C_OUT + co0) + m;
+                const v2u *xr = reinterpret_cast<const v2u *>(static_cast<const uint16_t *>(x_) + (size_t)i * C_IN + ci0) + m;
+#pragma unroll
+                for (int qo = 0; qo < QO; ++qo) dyw[qo][e] = t < n ? dyr[qo * 16] : v2u{0u, 0u};
+#pragma unroll
+                for (int qi = 0; qi < QI; ++qi) xw[qi][e] = t < n ? xr[qi * 16] : v2u{0u, 0u};
+            }
+            v4u bv[QI][4];
+#pragma unroll
+            for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                for (int qs = 0; qs < 4; ++qs)
+#pragma unroll
+                    for (int wd = 0; wd < 4; ++wd)
+                        bv[qi][qs][wd] = __builtin_amdgcn_perm(xw[qi][2 * wd + 1][qs >> 1], xw[qi][2 * wd][qs >> 1],
+                                                               (qs & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+            for (int qo = 0; qo < QO; ++qo)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    v4u av;
+#pragma unroll
+                    for (int wd = 0; wd < 4; ++wd)
+                        av[wd] = __builtin_amdgcn_perm(dyw[qo][2 * wd + 1][qd >> 1], dyw[qo][2 * wd][qd >> 1],
+                                                       (qd & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+                    for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                        for (int qs = 0; qs < 4; ++qs)
+                            acc[qo][qd][qi][qs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv[qi][qs]), acc[qo][qd][qi][qs], 0, 0, 0);
+                }
+        }
+        // flush: lane (m, g), register j of acc[qo][qd][qi][qs] is dW[co0 + 64 qo + 4 (4g + j) + qd][ci0 + 64 qi + 4m + qs]
+        float *dstp = part + (size_t)(first ? chunk_id : n_chunks + k) * C_OUT * C_IN;
+#pragma unroll
+        for (int qo = 0; qo < QO; ++qo)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+#pragma unroll
+                for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int co = co0 + 64 * qo + 4 * (4 * g + j) + qd;
+                        const int ci = ci0 + 64 * qi + 4 * m;
+                        *reinterpret_cast<v4f *>(dstp + (size_t)co * C_IN + ci) =
+                            v4f{acc[qo][qd][qi][0][j], acc[qo][qd][qi][1][j], acc[qo][qd][qi][2][j], acc[qo][qd][qi][3][j]};
+                    }
+        first = false;
+        p = q_end;
+        ++k;
+    }
+}
+
 // dw[k][e] = (partial of the run's head, if it starts inside a chunk) + partials of the chunks whose first
 // triplet lies in run k.  16 threads share one element: thread g adds chunks c0+g, c0+g+16, ... in
 // ascending order and the 16 sums are then added in order of g, so the result is reproducible.
@@ -226,8 +345,12 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     }
     float *part = static_cast<float *>(workspace);
     if (n_chunks > 0) {
-        weight_kernel<BF16, C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
-            a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
+        if constexpr (BF16 && C_IN >= 128 && C_OUT >= 128)
+            weight_wide_kernel<C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
+                a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
+        else
+            weight_kernel<BF16, C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
+                a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     dim3 grid((unsigned)ceil_div(n_elem, 16), (unsigned)a.K);
