@@ -19,10 +19,9 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 constexpr int WAVES = 4;
 
 
-// MFMA register layouts used below (wave64):
-//   v_mfma_f32_32x32x2_f32 :  A: lane (m = l%32, h = l/32) gives A[m][h];  B: lane (n, h) gives B[h][n]
-//   v_mfma_f32_32x32x16_bf16: A: lane (m, h) gives A[m][8h .. 8h+7];       B: lane (n, h) gives B[8h .. 8h+7][n]
-//   D (both): lane l, register j -> row 8*(j/4) + 4*(l/32) + j%4, column l%32.
+// MFMA register layout used by the fp32 kernel (wave64):
+//   v_mfma_f32_32x32x2_f32: A: lane (m = l%32, h = l/32) gives A[m][h];  B: lane (n, h) gives B[h][n];
+//   D: lane l, register j -> row 8*(j/4) + 4*(l/32) + j%4, column l%32.
 
 // ---------------------------------------------------------------------------------------------
 // Weight gradient (VVOR), Eq. (5).  Wave c owns triplets [c*chunk, (c+1)*chunk) of the (k, o, i)
@@ -30,12 +29,11 @@ constexpr int WAVES = 4;
 // accumulator is flushed and restarted.  Slots of the partial buffer:
 //   slot c               sum for the cell of the chunk's first triplet
 //   slot n_chunks + k    sum for cell k over the part of its run that starts inside a chunk
-// fp32: one MFMA step consumes 2 triplets: lane (c, h) supplies channel c of dy[o] and of x[i] of
-// triplet 2 s + h.  bf16: one step consumes 16 triplets; a lane reads one dword (2 channels) per
-// triplet and the even / odd channels form separate 32-wide blocks of the operand.
+// fp32 layers (this kernel): one MFMA step consumes 2 triplets: lane (c, h) supplies channel c of dy[o] and
+// of x[i] of triplet 2 s + h.  bf16 layers use weight_wide_kernel below.
+// Layers wider than one wave's accumulators: a wave owns a SUB_OUT x SUB_IN block of dW[k]; the waves that
+// share a chunk are consecutive, so their re-reads of the same rows are served by the L1 / L2 caches.
 // ---------------------------------------------------------------------------------------------
-// Wide layers: a wave owns a SUB_OUT x SUB_IN block of dW[k]; the n_sub waves that share a chunk are
-// consecutive, so their re-reads of the same rows are served by the L1 / L2 caches.
 template <bool BF16, int C_IN, int C_OUT, int SUB_IN, int SUB_OUT>
 __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 5 : 1) void weight_kernel(const void *__restrict__ x_, const void *__restrict__ dy_,
                                                             float *__restrict__ part,
@@ -86,7 +84,8 @@ __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 
             // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
             int32_t oi = 0;
             if (c < n) oi = h == 0 ? tri_o[b0 + c] : tri_i[b0 + c];
-            if constexpr (!BF16) {
+            static_assert(!BF16, "bf16 layers use weight_wide_kernel");
+            {
                 float a[NBO][NS], b[NBI][NS];
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
@@ -106,46 +105,6 @@ __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 
 #pragma unroll
                         for (int bi = 0; bi < NBI; ++bi)
                             acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bo][s], b[bi][s], acc[bo][bi], 0, 0, 0);
-            } else {
-                // block index of the operand = 2 * q + parity: channel 2 * (c + 32 q) + parity
-                constexpr int QO = SUB_OUT / 64, QI = SUB_IN / 64;
-#pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    uint32_t dyw[QO][8], xw[QI][8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int t = 16 * s + 8 * h + e;
-                        const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
-                        const uint32_t *dyr = static_cast<const uint32_t *>(dy_) + (size_t)o * (C_OUT / 2) + co0 / 2 + c;
-                        const uint32_t *xr = static_cast<const uint32_t *>(x_) + (size_t)i * (C_IN / 2) + ci0 / 2 + c;
-#pragma unroll
-                        for (int qo = 0; qo < QO; ++qo) dyw[qo][e] = t < n ? dyr[qo * 32] : 0u;
-#pragma unroll
-                        for (int qi = 0; qi < QI; ++qi) xw[qi][e] = t < n ? xr[qi * 32] : 0u;
-                    }
-                    v4u av[NBO], bv[NBI];
-#pragma unroll
-                    for (int qo = 0; qo < QO; ++qo)
-#pragma unroll
-                        for (int e2 = 0; e2 < 4; ++e2) {
-                            av[2 * qo][e2] = (dyw[qo][2 * e2] & 0xffffu) | (dyw[qo][2 * e2 + 1] << 16);
-                            av[2 * qo + 1][e2] = (dyw[qo][2 * e2] >> 16) | (dyw[qo][2 * e2 + 1] & 0xffff0000u);
-                        }
-#pragma unroll
-                    for (int qi = 0; qi < QI; ++qi)
-#pragma unroll
-                        for (int e2 = 0; e2 < 4; ++e2) {
-                            bv[2 * qi][e2] = (xw[qi][2 * e2] & 0xffffu) | (xw[qi][2 * e2 + 1] << 16);
-                            bv[2 * qi + 1][e2] = (xw[qi][2 * e2] >> 16) | (xw[qi][2 * e2 + 1] & 0xffff0000u);
-                        }
-#pragma unroll
-                    for (int bo = 0; bo < NBO; ++bo)
-#pragma unroll
-                        for (int bi = 0; bi < NBI; ++bi)
-                            acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av[bo]),
-                                                                                  __builtin_bit_cast(v8bf, bv[bi]),
-                                                                                  acc[bo][bi], 0, 0, 0);
-                }
             }
         }
         // flush
@@ -157,14 +116,7 @@ __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int r = 8 * (j / 4) + 4 * h + (j % 4);
-                    int co, ci;
-                    if constexpr (BF16) {
-                        co = co0 + 2 * (r + 32 * (bo >> 1)) + (bo & 1);
-                        ci = ci0 + 2 * (c + 32 * (bi >> 1)) + (bi & 1);
-                    } else {
-                        co = co0 + bo * 32 + r;
-                        ci = ci0 + bi * 32 + c;
-                    }
+                    const int co = co0 + bo * 32 + r, ci = ci0 + bi * 32 + c;
                     dstp[(size_t)co * C_IN + ci] = acc[bo][bi][j];
                 }
         first = false;
@@ -174,7 +126,7 @@ __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Wide bf16 layers: the same chunking, with v_mfma_f32_16x16x32_bf16 (A: lane (M = l%16, g = l/16) holds
+// bf16 layers: the same chunking, with v_mfma_f32_16x16x32_bf16 (A: lane (M = l%16, g = l/16) holds
 // A[M][8g .. 8g+7]; B: lane (N = l%16, g) holds B[8g .. 8g+7][N]; D: lane l, register j -> M = 4g + j,
 // N = l%16).  One step consumes 32 triplets; lane (m, g) reads 8 bytes = channels 4m .. 4m+3 (+ 64 per
 // 64-channel group) of the rows of triplets 8g .. 8g+7, so one load instruction covers four rows and the
@@ -345,7 +297,7 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     }
     float *part = static_cast<float *>(workspace);
     if (n_chunks > 0) {
-        if constexpr (BF16 && C_IN >= 128 && C_OUT >= 128)
+        if constexpr (BF16)
             weight_wide_kernel<C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
                 a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
         else
