@@ -126,6 +126,105 @@ __global__ __launch_bounds__(WAVES * 64, (!BF16 && C_IN == 32 && C_OUT == 32) ? 
 }
 
 // ---------------------------------------------------------------------------------------------
+// fp32 layers, second form: v_mfma_f32_16x16x4_f32 (A: lane (M = l%16, g = l/16) gives A[M][g]; B: lane
+// (N = l%16, g) gives B[g][N]; D: lane l, register j -> M = 4g + j, N = l%16).  Lane (m, g) reads 8 bytes =
+// channels 2m, 2m+1 (+ 32 per 32-channel group) of the rows of triplets g, 4 + g, ..., 28 + g of a batch of 32:
+// one load instruction covers four rows, half the address-unit work of one channel per lane, and the loaded
+// values are MFMA operands as they are (row / column m of operand (group, q) is channel 32 group + 2m + q).
+// ---------------------------------------------------------------------------------------------
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+template <int C_IN, int C_OUT>
+__global__ __launch_bounds__(WAVES * 64) void weight_f32_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                                                float *__restrict__ part,
+                                                                const int32_t *__restrict__ tri_o,
+                                                                const int32_t *__restrict__ tri_i,
+                                                                const int64_t *__restrict__ seg, int K,
+                                                                int64_t n_triplets, int chunk, int64_t n_chunks)
+{
+    constexpr int QO = C_OUT / 32, QI = C_IN / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int64_t chunk_id = (int64_t)blockIdx.x * WAVES + wave;
+    if (chunk_id >= n_chunks) return;
+    int64_t p = chunk_id * chunk;
+    int64_t p_end = p + chunk;
+    if (p_end > n_triplets) p_end = n_triplets;
+
+    // cell of the first triplet: the k with seg[k] <= p < seg[k+1]
+    int k = 0;
+    for (int kb = 0; kb < K; kb += 64) {
+        const int kk = kb + lane;
+        const bool hit = kk < K && seg[kk] <= p && p < seg[kk + 1];
+        const unsigned long long msk = __ballot(hit);
+        if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
+    }
+
+    v4f acc[QO][2][QI][2];
+    bool first = true;
+    while (p < p_end) {
+        int64_t q_end = seg[k + 1];
+        if (q_end > p_end) q_end = p_end;
+        if (q_end <= p) { ++k; continue; }   // empty run
+#pragma unroll
+        for (int a = 0; a < QO; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int c = 0; c < QI; ++c)
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) acc[a][b][c][d] = v4f{0.f, 0.f, 0.f, 0.f};
+
+        for (int64_t b0 = p; b0 < q_end; b0 += 32) {
+            const int n = (int)(q_end - b0 < 32 ? q_end - b0 : 32);
+            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
+            int32_t oi = 0;
+            if ((lane & 31) < n) oi = lane < 32 ? tri_o[b0 + lane] : tri_i[b0 + lane - 32];
+            v2f dyw[QO][8], xw[QI][8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int t = 4 * e + g;
+                const int32_t o = __shfl(oi, t, 64), i = __shfl(oi, 32 + t, 64);
+                const v2f *dyr = reinterpret_cast<const v2f *>(dy + (size_t)o * C_OUT) + m;
+                const v2f *xr = reinterpret_cast<const v2f *>(x + (size_t)i * C_IN) + m;
+#pragma unroll
+                for (int qo = 0; qo < QO; ++qo) dyw[qo][e] = t < n ? dyr[qo * 16] : v2f{0.f, 0.f};
+#pragma unroll
+                for (int qi = 0; qi < QI; ++qi) xw[qi][e] = t < n ? xr[qi * 16] : v2f{0.f, 0.f};
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int qo = 0; qo < QO; ++qo)
+#pragma unroll
+                    for (int qd = 0; qd < 2; ++qd)
+#pragma unroll
+                        for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                            for (int qs = 0; qs < 2; ++qs)
+                                acc[qo][qd][qi][qs] = __builtin_amdgcn_mfma_f32_16x16x4f32(dyw[qo][e][qd], xw[qi][e][qs],
+                                                                                           acc[qo][qd][qi][qs], 0, 0, 0);
+        }
+        // flush: lane (m, g), register j of acc[qo][qd][qi][qs] is dW[32 qo + 2 (4g + j) + qd][32 qi + 2m + qs]
+        float *dstp = part + (size_t)(first ? chunk_id : n_chunks + k) * C_OUT * C_IN;
+#pragma unroll
+        for (int qo = 0; qo < QO; ++qo)
+#pragma unroll
+            for (int qd = 0; qd < 2; ++qd)
+#pragma unroll
+                for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int co = 32 * qo + 2 * (4 * g + j) + qd, ci = 32 * qi + 2 * m;
+                        *reinterpret_cast<v2f *>(dstp + (size_t)co * C_IN + ci) = v2f{acc[qo][qd][qi][0][j], acc[qo][qd][qi][1][j]};
+                    }
+        first = false;
+        p = q_end;
+        ++k;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // bf16 layers: the same chunking, with v_mfma_f32_16x16x32_bf16 (A: lane (M = l%16, g = l/16) holds
 // A[M][8g .. 8g+7]; B: lane (N = l%16, g) holds B[8g .. 8g+7][N]; D: lane l, register j -> M = 4g + j,
 // N = l%16).  One step consumes 32 triplets; lane (m, g) reads 8 bytes = channels 4m .. 4m+3 (+ 64 per
@@ -297,7 +396,11 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     }
     float *part = static_cast<float *>(workspace);
     if (n_chunks > 0) {
-        if constexpr (BF16)
+        if constexpr (!BF16 && SUB_IN == C_IN && SUB_OUT == C_OUT)
+            weight_f32_kernel<C_IN, C_OUT><<<(unsigned)ceil_div(n_chunks, WAVES), WAVES * 64, 0, stream>>>(
+                static_cast<const float *>(a.feat), static_cast<const float *>(a.dense), part, tri_o, a.gather, seg, a.K,
+                a.n_triplets, chunk, n_chunks);
+        else if constexpr (BF16)
             weight_wide_kernel<C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
                 a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
         else
