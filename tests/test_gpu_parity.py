@@ -250,3 +250,42 @@ def test_scene5_full_size_sampled(pcpp):
     uo, inv = np.unique(o2, return_inverse=True)
     ref, scale = oracle_bwd_input(dy[uo], w, inv.astype(np.int32), i2, k2, len(si))
     assert_close(gx[torch.from_numpy(si).cuda()].cpu().numpy(), ref, scale, tol, "scene5 bwd_input (sampled inputs)")
+
+
+def test_build_with_and_without_kept_neighbours(pcpp):
+    """The second pass either ranks the neighbours the count pass kept (large workspace) or searches again
+    (minimal workspace, or lists longer than the kept part): same triplets and same plan either way, and both
+    equal to the oracle's list."""
+    rng = np.random.default_rng(77)
+    # a dense blob among sparse points: some centres have far more neighbours than twice the mean
+    pts = np.concatenate([rng.random((3000, 3)) * 2.0, 0.9 + rng.random((500, 3)) * 0.08]).astype(np.float32)
+    out = pts[::3].copy()
+    r, t = 0.12, 3
+    o, i, k, seg = oracle.build_triplets(pts, out, r, t)
+    L = pcpp.library()
+    din, dout = dev(pts), dev(out)
+    small = torch.empty(L.pcpp_build_triplets_workspace_bytes(len(pts), len(out), t), dtype=torch.uint8, device="cuda")
+    large = torch.empty(L.pcpp_build_triplets_workspace_bytes_for(len(pts), len(out), t, len(o)), dtype=torch.uint8,
+                        device="cuda")
+    assert large.numel() > small.numel()
+    # capacity given: the binding keeps a workspace that is large enough, so the minimal one is passed through
+    # the C ABI directly
+    import ctypes
+    from paper_2511_23227_amd import binding as B
+    results = []
+    for ws in (small, large):
+        tri = [torch.empty(len(o), dtype=torch.int32, device="cuda") for _ in range(3)]
+        sg = torch.empty(t ** 3 + 1, dtype=torch.int64, device="cuda")
+        flags = B.PLAN_FWD | B.PLAN_BWD_INPUT
+        plan = torch.zeros(L.pcpp_plan_bytes(len(pts), len(out), t, len(o), flags), dtype=torch.uint8, device="cuda")
+        n = ctypes.c_int64(0)
+        rc = L.pcpp_build_triplets(B._ptr(din), len(pts), B._ptr(dout), len(out), float(r), t, B._ptr(tri[0]),
+                                   B._ptr(tri[1]), B._ptr(tri[2]), len(o), B._ptr(sg), ctypes.byref(n), B._ptr(plan),
+                                   plan.numel(), flags, B._ptr(ws), ws.numel(), B._stream())
+        assert rc == 0, L.pcpp_last_error()
+        torch.cuda.synchronize()
+        assert n.value == len(o)
+        assert np.array_equal(tri[0].cpu().numpy(), o) and np.array_equal(tri[1].cpu().numpy(), i)
+        assert np.array_equal(tri[2].cpu().numpy(), k) and np.array_equal(sg.cpu().numpy(), seg)
+        results.append(plan.cpu().numpy()[256:])         # everything after the header
+    assert np.array_equal(results[0], results[1])
