@@ -19,9 +19,6 @@ constexpr int CELL_BIAS = 1 << 20;
 constexpr double CELL_CLAMP = (double)((1 << 20) - 2);   // +-1 stencil steps stay inside 21 bits
 constexpr int SEARCH_THREADS = 1024;                      // 16 waves share a tile of 64 centres: 4 centres each
 constexpr int SEARCH_WAVES = SEARCH_THREADS / 64;
-// Centres a wave of the count pass handles at once.  More would overlap their dependent grid loads, but the
-// registers that costs lower the occupancy below two blocks per CU, which measured worse on every scene.
-constexpr int COUNT_ILP = 1;
 constexpr int LIST_CAP_MAX = 512;                         // neighbours of one centre kept in LDS (per wave)
 
 __device__ inline uint32_t hash_key(unsigned long long k)
@@ -143,8 +140,16 @@ struct Candidates {
     }
 
     // Candidate number idx (idx may differ per lane).  Returns whether it is a neighbour;
-    // b = its original index, k = its kernel cell.
+    // b = its original index, k = its kernel cell.  With MIRROR, k2 = the cell of the opposite offset, i.e.
+    // the cell this pair falls in when the roles of the two points are swapped.
     __device__ inline bool fetch(uint32_t idx, const GridView &g, const QueryParams &q, int &b, int &k) const
+    {
+        int k2;
+        return fetch2<false>(idx, g, q, b, k, k2);
+    }
+
+    template <bool MIRROR>
+    __device__ inline bool fetch2(uint32_t idx, const GridView &g, const QueryParams &q, int &b, int &k, int &k2) const
     {
         const bool in_range = idx < total;
         const uint32_t id = in_range ? idx : 0u;
@@ -159,7 +164,7 @@ struct Candidates {
         const uint32_t s = __shfl(my_start, j, 64);
         const uint32_t e = __shfl(my_excl, j, 64);
         bool hit = false;
-        b = 0; k = 0;
+        b = 0; k = 0; k2 = 0;
         if (in_range) {
             const float4 p = g.pts[s + (id - e)];
             b = __float_as_int(p.w);
@@ -177,6 +182,16 @@ struct Candidates {
             int ky = uy < 0.0 ? 0 : (int)fmin(uy, (double)tm1);
             int kz = uz < 0.0 ? 0 : (int)fmin(uz, (double)tm1);
             k = (kx * q.t + ky) * q.t + kz;
+            if constexpr (MIRROR) {
+                // the swapped subtraction gives exactly the negated offset
+                const double vx = floor(__dmul_rn(__dadd_rn(-dx, q.R), q.inv_cell));
+                const double vy = floor(__dmul_rn(__dadd_rn(-dy, q.R), q.inv_cell));
+                const double vz = floor(__dmul_rn(__dadd_rn(-dz, q.R), q.inv_cell));
+                const int mx = vx < 0.0 ? 0 : (int)fmin(vx, (double)tm1);
+                const int my = vy < 0.0 ? 0 : (int)fmin(vy, (double)tm1);
+                const int mz = vz < 0.0 ? 0 : (int)fmin(vz, (double)tm1);
+                k2 = (mx * q.t + my) * q.t + mz;
+            }
         }
         return hit;
     }
@@ -187,79 +202,81 @@ constexpr int HIT_INDEX_BITS = 24;         // a stored hit = cell << 24 | candid
 constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
 
 // ---- pass 1: neighbours per (cell k, centre) --------------------------------------------------
-// One block per tile of TILE centres, one wave per centre at a time.
+// One block per tile of TILE centres, one wave per centre at a time.  Outputs of one side:
 //   tile_cnt   [n_tiles][K][TILE]   (may be NULL: totals only)
 //   tile_k_cnt [K * n_tiles]        k-major, input of the prefix sum
-template <bool SWAP>
+//   hits       [n_centres][hit_stride] (may be NULL): every centre's first neighbours, cell << 24 | index
+// With BOTH (a cloud queried against itself) the same pass also fills the tables of the side with the roles
+// swapped: the pair (centre c, candidate b) is the pair (centre c, other point b) of that side too, in the cell
+// of the opposite offset.
+struct CountOut {
+    uint32_t *tile_cnt, *tile_k_cnt, *hits;
+};
+
+template <bool SWAP, bool BOTH>
 __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__restrict__ centres, int64_t n_centres,
                                                               GridView g, QueryParams q, int K, int64_t n_tiles,
-                                                              uint32_t *__restrict__ tile_cnt,
-                                                              uint32_t *__restrict__ tile_k_cnt,
-                                                              uint32_t *__restrict__ hits, uint32_t hit_stride)
+                                                              CountOut side, CountOut mirror, uint32_t hit_stride)
 {
-    extern __shared__ uint32_t tbl[];          // [K][TILE]
-    __shared__ uint32_t stage[SEARCH_WAVES * COUNT_ILP * SMALL_LIST];   // hit lists on their way to memory
+    extern __shared__ uint32_t tbl[];          // [K][TILE], with BOTH followed by the mirror side's [K][TILE]
+    __shared__ uint32_t stage[(BOTH ? 2 : 1) * SEARCH_WAVES * SMALL_LIST];   // hit lists on their way to memory
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
-    for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
+    uint32_t *tbl2 = tbl + K * TILE;
+    uint32_t *mine = stage + wave * SMALL_LIST, *mine2 = stage + (SEARCH_WAVES + wave) * SMALL_LIST;
+    for (int idx = threadIdx.x; idx < (BOTH ? 2 : 1) * K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
     __syncthreads();
-    for (int al0 = wave; al0 < TILE; al0 += SEARCH_WAVES * COUNT_ILP) {
-        Candidates<SWAP> c[COUNT_ILP];
-        uint32_t most = 0;
-#pragma unroll
-        for (int u = 0; u < COUNT_ILP; ++u) {
-            const int al = al0 + u * SEARCH_WAVES;
-            const int64_t a = tile * TILE + al;
-            const bool ok = al < TILE && a < n_centres;            // wave-uniform
-            c[u].open(centres, ok ? a : 0, g, lane);
-            if (!ok) c[u].total = 0;
-            most = c[u].total > most ? c[u].total : most;
-        }
-        uint32_t filled[COUNT_ILP];
-#pragma unroll
-        for (int u = 0; u < COUNT_ILP; ++u) filled[u] = 0;
-        for (uint32_t base = 0; base < most; base += 64) {
-            int b[COUNT_ILP], k[COUNT_ILP];
-            bool hit[COUNT_ILP];
-#pragma unroll
-            for (int u = 0; u < COUNT_ILP; ++u) {
-                hit[u] = c[u].fetch(base + lane, g, q, b[u], k[u]);
-                if (hit[u]) atomicAdd(&tbl[k[u] * TILE + al0 + u * SEARCH_WAVES], 1u);
+    const bool keep = side.hits != nullptr;
+    for (int al = wave; al < TILE; al += SEARCH_WAVES) {
+        const int64_t a = tile * TILE + al;
+        if (a >= n_centres) break;                 // wave-uniform
+        Candidates<SWAP> c;
+        c.open(centres, a, g, lane);
+        uint32_t filled = 0;
+        for (uint32_t base = 0; base < c.total; base += 64) {
+            int b, k, k2;
+            const bool hit = c.template fetch2<BOTH>(base + lane, g, q, b, k, k2);
+            if (hit) {
+                atomicAdd(&tbl[k * TILE + al], 1u);
+                if constexpr (BOTH) atomicAdd(&tbl2[k2 * TILE + al], 1u);
             }
-            if (hits) {                            // every centre's first hit_stride neighbours, in arrival order
-#pragma unroll
-                for (int u = 0; u < COUNT_ILP; ++u) {
-                    const unsigned long long m = __ballot(hit[u]);
-                    const uint32_t slot = filled[u] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-                    if (hit[u] && slot < hit_stride)
-                        stage[(wave * COUNT_ILP + u) * SMALL_LIST + slot] = ((uint32_t)k[u] << HIT_INDEX_BITS) | (uint32_t)b[u];
-                    filled[u] += (uint32_t)__popcll(m);
+            if (keep) {                            // the centre's first hit_stride neighbours, in arrival order
+                const unsigned long long m = __ballot(hit);
+                const uint32_t slot = filled + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                if (hit && slot < hit_stride) {
+                    mine[slot] = ((uint32_t)k << HIT_INDEX_BITS) | (uint32_t)b;
+                    if constexpr (BOTH) mine2[slot] = ((uint32_t)k2 << HIT_INDEX_BITS) | (uint32_t)b;
                 }
+                filled += (uint32_t)__popcll(m);
             }
         }
-        if (hits) {                                // one contiguous write per centre
+        if (keep) {                                // one contiguous write per centre
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int u = 0; u < COUNT_ILP; ++u) {
-                const uint32_t n = filled[u] < hit_stride ? filled[u] : hit_stride;
-                uint32_t *dst = hits + (size_t)(tile * TILE + al0 + u * SEARCH_WAVES) * hit_stride;
-                for (uint32_t e = lane; e < n; e += 64) dst[e] = stage[(wave * COUNT_ILP + u) * SMALL_LIST + e];
+            const uint32_t n = filled < hit_stride ? filled : hit_stride;
+            for (uint32_t e = lane; e < n; e += 64) {
+                side.hits[(size_t)a * hit_stride + e] = mine[e];
+                if constexpr (BOTH) mirror.hits[(size_t)a * hit_stride + e] = mine2[e];
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
     }
     __syncthreads();
-    if (tile_cnt) {
-        uint32_t *dst = tile_cnt + (size_t)tile * K * TILE;
-        for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) dst[idx] = tbl[idx];
-    }
-    for (int k = wave; k < K; k += SEARCH_WAVES) {
-        uint32_t v = tbl[k * TILE + lane];
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-        if (lane == 0) tile_k_cnt[(size_t)k * n_tiles + tile] = v;
+    for (int sd = 0; sd < (BOTH ? 2 : 1); ++sd) {
+        const CountOut &o = sd == 0 ? side : mirror;
+        const uint32_t *t = sd == 0 ? tbl : tbl2;
+        if (o.tile_cnt) {
+            uint32_t *dst = o.tile_cnt + (size_t)tile * K * TILE;
+            for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) dst[idx] = t[idx];
+        }
+        for (int k = wave; k < K; k += SEARCH_WAVES) {
+            uint32_t v = t[k * TILE + lane];
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+            if (lane == 0) o.tile_k_cnt[(size_t)k * n_tiles + tile] = v;
+        }
     }
 }
 
@@ -727,9 +744,9 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     const size_t lds = (size_t)K * TILE * sizeof(uint32_t);
     if (lds > (size_t)32 * 1024) {
         // large t: the per-tile table plus the neighbour lists exceed the default dynamic LDS limit
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false>),
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<true>),
+        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<true, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -743,10 +760,19 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     // plan layout depends on |T|, which is only known after the prefix sum.
     uint32_t *f_ptr = reinterpret_cast<uint32_t *>(ws + bs.fwd_ptr_off);
     uint32_t *f_cnt = reinterpret_cast<uint32_t *>(ws + bs.fwd_cnt_off);
+    // A cloud queried against itself: one pass counts both sides (while two [K][64] tables fit beside the lists
+    // in the LDS share of two blocks per CU).
+    const bool one_pass = want_bwd_plan && out_xyz == in_xyz && n_out == n_in && 2 * lds <= (size_t)32 * 1024;
+    uint32_t *b_cnt = reinterpret_cast<uint32_t *>(ws + bs.bwd_cnt_off);
+    uint32_t *b_sum = reinterpret_cast<uint32_t *>(ws + bs.bwd_ptr_off);   // per-(k, tile) sums of the swapped side
     if (nt_o > 0) {
-        query_count<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o,
-                                                                         count_only ? nullptr : f_cnt, f_ptr, f_hits,
-                                                                         bs.fwd_stride);
+        const CountOut fwd_out{count_only ? nullptr : f_cnt, f_ptr, f_hits};
+        if (one_pass)
+            query_count<false, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+                out_xyz, n_out, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride);
+        else
+            query_count<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+                out_xyz, n_out, grid_in, q, K, nt_o, fwd_out, CountOut{nullptr, nullptr, nullptr}, bs.fwd_stride);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if ((rc = scan_exclusive_u32(f_ptr, f_ptr, (int64_t)K * nt_o, scan_scratch, total_dev, stream)) != PCPP_OK) return rc;
@@ -803,15 +829,15 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
                 return rc;
         }
         uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
-        uint32_t *b_cnt = reinterpret_cast<uint32_t *>(ws + bs.bwd_cnt_off);
         uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
         int32_t *b_gather = reinterpret_cast<int32_t *>(pb + pl.bwd.gather_off);
-        if (nt_i > 0) {
-            query_count<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
-                                                                            b_ptr, b_hits, bs.bwd_stride);
+        if (nt_i > 0 && !one_pass) {
+            query_count<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
+                in_xyz, n_in, grid_out, q, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, CountOut{nullptr, nullptr, nullptr},
+                bs.bwd_stride);
             PCPP_HIP_CHECK(hipGetLastError());
         }
-        if ((rc = scan_exclusive_u32(b_ptr, b_ptr, (int64_t)K * nt_i, scan_scratch, total_dev + 1, stream)) != PCPP_OK)
+        if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch, total_dev + 1, stream)) != PCPP_OK)
             return rc;
         if (nt_i > 0) {
             query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
