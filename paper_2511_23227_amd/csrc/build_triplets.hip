@@ -45,6 +45,17 @@ __device__ inline unsigned long long pack_key(int cx, int cy, int cz)
 
 // ---- hashed grid over the candidate set ------------------------------------------------------
 
+// empty table: no keys, zero populations (slots + 1 entries, the input of the prefix sum), zero cursors
+__global__ __launch_bounds__(256) void grid_clear(unsigned long long *__restrict__ keys, uint32_t *__restrict__ cnt,
+                                                  uint32_t *__restrict__ cursor, int64_t slots)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i <= slots; i += stride) {
+        cnt[i] = 0u;
+        if (i < slots) { keys[i] = EMPTY_KEY; cursor[i] = 0u; }
+    }
+}
+
 __global__ __launch_bounds__(256) void grid_insert(const float *__restrict__ xyz, int64_t n, double inv_g,
                                                    unsigned long long *__restrict__ keys,
                                                    uint32_t *__restrict__ slot_cnt, uint32_t mask,
@@ -592,9 +603,12 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
     auto *point_slot = reinterpret_cast<uint32_t *>(ws + gs.point_slot_off);
     auto *pts = reinterpret_cast<float4 *>(ws + gs.pts_off);
     int rc;
-    if ((rc = fill_u64(keys, EMPTY_KEY, gs.slots, stream)) != PCPP_OK) return rc;
-    if ((rc = fill_u32(cnt, 0u, gs.slots + 1, stream)) != PCPP_OK) return rc;
-    if ((rc = fill_u32(cursor, 0u, gs.slots, stream)) != PCPP_OK) return rc;
+    {
+        int64_t blocks = ceil_div(gs.slots + 1, 256);
+        if (blocks > 4096) blocks = 4096;
+        grid_clear<<<(unsigned)blocks, 256, 0, stream>>>(keys, cnt, cursor, gs.slots);
+        PCPP_HIP_CHECK(hipGetLastError());
+    }
     if (n > 0) {
         const unsigned blocks = (unsigned)ceil_div(n, 256);
         grid_insert<<<blocks, 256, 0, stream>>>(xyz, n, inv_g, keys, cnt, (uint32_t)(gs.slots - 1), point_slot);
