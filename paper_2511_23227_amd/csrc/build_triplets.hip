@@ -294,7 +294,8 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
 // ---- pass 2: write every triplet to its place in (k, centre, other) order ----------------------
 //   tile_cnt  [n_tiles][K][TILE]  counts from pass 1
 //   tile_ptr  [K * n_tiles + 1]   exclusive prefix sum of tile_k_cnt
-//   out_c / out_b / out_k: centre index, candidate index, cell of each triplet (any may be NULL)
+//   out_c / out_b / out_k: centre index, candidate index, cell of each triplet (any may be NULL), out_cap entries each
+//                          (the pass is launched before the host has compared the count with the capacity)
 // One wave per centre at a time.  The centre's neighbours are compacted into per-cell buckets of an
 // LDS list with wave ballots and prefix popcounts (the bucket sizes are the counts of pass 1), then
 // each neighbour's rank inside its bucket (number of smaller candidate indices) gives its final slot,
@@ -309,7 +310,8 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                                                              int32_t *__restrict__ out_c, int32_t *__restrict__ out_b,
                                                              int32_t *__restrict__ out_k,
                                                              uint32_t *__restrict__ run_start_out, int list_cap,
-                                                             const uint32_t *__restrict__ hits, uint32_t hit_stride)
+                                                             const uint32_t *__restrict__ hits, uint32_t hit_stride,
+                                                             uint32_t out_cap)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
     __shared__ uint32_t list_all[SEARCH_WAVES][LIST_CAP_MAX];
@@ -373,9 +375,11 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                 for (; e2 < n; ++e2) rank += (list[e2] - kbase) < rel ? 1u : 0u;
                 const int k = (int)(key >> HIT_INDEX_BITS);
                 const uint32_t pos = tbl[k * TILE + al] + rank;
-                if (out_c) out_c[pos] = (int32_t)a;
-                if (out_b) out_b[pos] = (int32_t)rel;
-                if (out_k) out_k[pos] = k;
+                if (pos < out_cap) {
+                    if (out_c) out_c[pos] = (int32_t)a;
+                    if (out_b) out_b[pos] = (int32_t)rel;
+                    if (out_k) out_k[pos] = k;
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -426,9 +430,11 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                 for (; e2 < n; ++e2) rank += ((keys[e2] - kbase) < rel) ? 1u : 0u;
                 const int k = (int)(key >> 32);
                 const uint32_t pos = tbl[k * TILE + al] + rank;
-                if (out_c) out_c[pos] = (int32_t)a;
-                if (out_b) out_b[pos] = (int32_t)(uint32_t)key;
-                if (out_k) out_k[pos] = k;
+                if (pos < out_cap) {
+                    if (out_c) out_c[pos] = (int32_t)a;
+                    if (out_b) out_b[pos] = (int32_t)(uint32_t)key;
+                    if (out_k) out_k[pos] = k;
+                }
             }
         } else if (n <= (uint32_t)list_cap) {
             for (uint32_t base = 0; base < c.total; base += 64) {
@@ -474,7 +480,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                             for (int u = 0; u < 8; ++u) rank += v[u] < mine ? 1u : 0u;
                         }
                         for (; e2 < nk; ++e2) rank += list[b0 + e2] < mine ? 1u : 0u;
-                        if (e < nk) {
+                        if (e < nk && run0 + rank < out_cap) {
                             const uint32_t pos = run0 + rank;
                             if (out_c) out_c[pos] = (int32_t)a;
                             if (out_b) out_b[pos] = (int32_t)mine;
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                     const bool hit2 = c.fetch(idx2, g, q, b2, k2);
                     rank += (hit2 && k2 == k && b2 < b) ? 1u : 0u;
                 }
-                if (hit) {
+                if (hit && tbl[k * TILE + al] + rank < out_cap) {
                     const uint32_t pos = tbl[k * TILE + al] + rank;
                     if (out_c) out_c[pos] = (int32_t)a;
                     if (out_b) out_b[pos] = b;
@@ -629,6 +635,18 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
 }
 
 int g_list_cap = LIST_CAP_MAX;
+
+// Per host thread: pinned landing place of |T| and the event that says it has arrived.  Created on first use
+// and kept until the process ends.
+struct HostTotal {
+    unsigned long long *pinned = nullptr;
+    hipEvent_t ready = nullptr;
+};
+HostTotal &host_total()
+{
+    static thread_local HostTotal t;
+    return t;
+}
 
 }  // namespace
 
@@ -791,33 +809,41 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     }
     if ((rc = scan_exclusive_u32(f_ptr, f_ptr, (int64_t)K * nt_o, scan_scratch, total_dev, stream)) != PCPP_OK) return rc;
 
-    unsigned long long total = 0;
-    PCPP_HIP_CHECK(hipMemcpyAsync(&total, total_dev, sizeof(total), hipMemcpyDeviceToHost, stream));
-    PCPP_HIP_CHECK(hipStreamSynchronize(stream));
-    *n_triplets = (int64_t)total;
-    if (total >= (unsigned long long)INT32_MAX) {
-        set_error("pcpp_build_triplets: %llu triplets; the library indexes at most 2^31-1", total);
-        return PCPP_ERR_UNSUPPORTED;
+    // |T| travels to pinned host memory behind an event, so that the host can pick it up while the second
+    // pass is already running; that pass guards its writes with the capacities instead of waiting for the check.
+    HostTotal &ht = host_total();
+    if (!ht.pinned) {
+        PCPP_HIP_CHECK(hipHostMalloc(reinterpret_cast<void **>(&ht.pinned), 64, hipHostMallocDefault));
+        PCPP_HIP_CHECK(hipEventCreateWithFlags(&ht.ready, hipEventDisableTiming));
     }
-    if (count_only) return PCPP_OK;
-    if ((int64_t)total > capacity) {
-        set_error("pcpp_build_triplets: %llu triplets but capacity is %lld", total, (long long)capacity);
-        return PCPP_ERR_CAPACITY;
-    }
-    PlanLayout pl;
-    if (plan) {
-        pl = plan_layout(n_in, n_out, K, (int64_t)total, plan_flags);
-        if (plan_bytes < pl.bytes) {
-            set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs %zu", plan_bytes, pl.bytes);
-            return PCPP_ERR_WORKSPACE;
+    PCPP_HIP_CHECK(hipMemcpyAsync(ht.pinned, total_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, stream));
+    PCPP_HIP_CHECK(hipEventRecord(ht.ready, stream));
+    auto wait_total = [&](unsigned long long &total) -> int {
+        PCPP_HIP_CHECK(hipEventSynchronize(ht.ready));
+        total = *ht.pinned;
+        *n_triplets = (int64_t)total;
+        if (total >= (unsigned long long)INT32_MAX) {
+            set_error("pcpp_build_triplets: %llu triplets; the library indexes at most 2^31-1", total);
+            return PCPP_ERR_UNSUPPORTED;
         }
+        return PCPP_OK;
+    };
+    unsigned long long total = 0;
+    if (count_only) return wait_total(total);
+
+    // the offsets inside the plan do not depend on |T| (the only array that does comes last)
+    const PlanLayout pl = plan ? plan_layout(n_in, n_out, K, 0, plan_flags) : PlanLayout{};
+    if (plan && plan_bytes < pl.bytes) {
+        set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs at least %zu", plan_bytes, pl.bytes);
+        return PCPP_ERR_WORKSPACE;
     }
+    const uint32_t tri_cap = (uint32_t)(capacity < (int64_t)INT32_MAX ? capacity : (int64_t)INT32_MAX);
     char *pb = static_cast<char *>(plan);
     if (nt_o > 0) {
         uint32_t *f_runs = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
         query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
                                                                         f_ptr, tri_o, tri_i, tri_k, f_runs,
-                                                                        g_list_cap, f_hits, bs.fwd_stride);
+                                                                        g_list_cap, f_hits, bs.fwd_stride, tri_cap);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if (nt_o > 0) {
@@ -845,6 +871,8 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
         uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
         int32_t *b_gather = reinterpret_cast<int32_t *>(pb + pl.bwd.gather_off);
+        const size_t gather_room = (plan_bytes - pl.bwd.gather_off) / 4;
+        const uint32_t gather_cap = (uint32_t)(gather_room < (size_t)tri_cap ? gather_room : (size_t)tri_cap);
         if (nt_i > 0 && !one_pass) {
             query_count<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
                 in_xyz, n_in, grid_out, q, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, CountOut{nullptr, nullptr, nullptr},
@@ -856,8 +884,21 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         if (nt_i > 0) {
             query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
                                                                            b_ptr, nullptr, b_gather, nullptr, b_runs,
-                                                                           g_list_cap, b_hits, bs.bwd_stride);
+                                                                           g_list_cap, b_hits, bs.bwd_stride, gather_cap);
             PCPP_HIP_CHECK(hipGetLastError());
+        }
+    }
+    // everything is queued; now compare the count with what the caller provided
+    if ((rc = wait_total(total)) != PCPP_OK) return rc;
+    if ((int64_t)total > capacity) {
+        set_error("pcpp_build_triplets: %llu triplets but capacity is %lld", total, (long long)capacity);
+        return PCPP_ERR_CAPACITY;
+    }
+    if (plan) {
+        const size_t need = plan_layout(n_in, n_out, K, (int64_t)total, plan_flags).bytes;
+        if (plan_bytes < need) {
+            set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs %zu", plan_bytes, need);
+            return PCPP_ERR_WORKSPACE;
         }
     }
     return PCPP_OK;
