@@ -145,11 +145,16 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        T = step(True)
+        T = step(False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     assert T.n_triplets == n_t
+    # per-op times: the same steps once more with events on the launch stream between the ops (outside the timed
+    # region: every event record costs a few microseconds of GPU time)
+    for _ in range(args.steps):
+        T = step(True)
+    torch.cuda.synchronize()
 
     op_ms = {nm: float(np.mean([ev[j].elapsed_time(ev[j + 1]) for ev in events])) for j, nm in enumerate(names)}
 
