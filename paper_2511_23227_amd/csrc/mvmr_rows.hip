@@ -99,12 +99,11 @@ __global__ void pack_w_split_kernel(const float *__restrict__ w, uint16_t *__res
     }
 }
 
-// Waves per SIMD the register allocation must leave room for: the bf16 64 -> 64 layer is bound by memory
-// latency and sits just above a register-count step without this (the fp32 32 -> 32 layer, three registers
-// above the next step, loses more to the spills than it gains).
+// Waves per SIMD the register allocation must leave room for: these two layers are bound by memory latency
+// and sit just above a register-count step without this.
 constexpr int rows_min_waves(bool bf16, int c_src, int c_dst)
 {
-    return (bf16 && c_src == 64 && c_dst == 64) ? 3 : 1;
+    return (!bf16 && c_src == 32 && c_dst == 32) ? 4 : ((bf16 && c_src == 64 && c_dst == 64) ? 3 : 1);
 }
 
 template <bool BF16, int C_SRC, int C_DST, int NW, typename TOut>
@@ -196,10 +195,11 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
             // W[k] fragments for stage 2, requested now so that they arrive during stage 1
             const v4u *wk = wfrag + (size_t)k * NB * NPC * 64;
             v4u bw[NB][NPC];
+            constexpr int NPC_EARLY = SPLIT ? NPC / 2 : NPC;   // the split form fetches its second half after stage 1
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int pc = 0; pc < NPC; ++pc) bw[b][pc] = wk[(b * NPC + pc) * 64];
+                for (int pc = 0; pc < NPC_EARLY; ++pc) bw[b][pc] = wk[(b * NPC + pc) * 64];
             for (uint32_t g0 = 0; g0 < n; g0 += 64) {
                 if (g0 != 0) {                       // source rows of the next 64 triplets
                     const uint32_t p = bs_c + g0 + lane;
@@ -287,27 +287,31 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
                                 __builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, bw[b][s * 2 + s2]), acc[b], 0, 0, 0);
                     }
             } else if constexpr (SPLIT) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int pc = NPC_EARLY; pc < NPC; ++pc) bw[b][pc] = wk[(b * NPC + pc) * 64];
                 // S = s1 + s2 + s3 and W = w1 + w2 + w3 exactly, each term a bf16; the six products of weight
                 // 2^-16 or more relative to s1 w1 are accumulated in fp32, smallest first.  Registers 8 kap ..
                 // 8 kap + 7 of lane (centre, h) are the channels 8 (2 kap + e/4) + 4 h + e%4 of reduction step kap.
                 static_assert(NG == 1, "split stage 2 is written for 32 source channels");
-                uint32_t t1[16], t2[16], t3[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const float x = d1[0][j];
-                    t1[j] = __float_as_uint(x) & 0xffff0000u;
-                    const float r1 = x - __uint_as_float(t1[j]);
-                    t2[j] = __float_as_uint(r1) & 0xffff0000u;
-                    t3[j] = __float_as_uint(r1 - __uint_as_float(t2[j]));
-                }
 #pragma unroll
                 for (int kap = 0; kap < 2; ++kap) {
+                    uint32_t t1[8], t2[8], t3[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float x = d1[0][8 * kap + j];
+                        t1[j] = __float_as_uint(x) & 0xffff0000u;
+                        const float r1 = x - __uint_as_float(t1[j]);
+                        t2[j] = __float_as_uint(r1) & 0xffff0000u;
+                        t3[j] = __float_as_uint(r1 - __uint_as_float(t2[j]));
+                    }
                     v4u a1, a2, a3;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        a1[q] = __builtin_amdgcn_perm(t1[8 * kap + 2 * q + 1], t1[8 * kap + 2 * q], 0x07060302u);
-                        a2[q] = __builtin_amdgcn_perm(t2[8 * kap + 2 * q + 1], t2[8 * kap + 2 * q], 0x07060302u);
-                        a3[q] = __builtin_amdgcn_perm(t3[8 * kap + 2 * q + 1], t3[8 * kap + 2 * q], 0x07060302u);
+                        a1[q] = __builtin_amdgcn_perm(t1[2 * q + 1], t1[2 * q], 0x07060302u);
+                        a2[q] = __builtin_amdgcn_perm(t2[2 * q + 1], t2[2 * q], 0x07060302u);
+                        a3[q] = __builtin_amdgcn_perm(t3[2 * q + 1], t3[2 * q], 0x07060302u);
                     }
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
