@@ -289,3 +289,69 @@ def test_build_with_and_without_kept_neighbours(pcpp):
         assert np.array_equal(tri[2].cpu().numpy(), k) and np.array_equal(sg.cpu().numpy(), seg)
         results.append(plan.cpu().numpy()[256:])         # everything after the header
     assert np.array_equal(results[0], results[1])
+
+
+@pytest.mark.parametrize("case", [
+    dict(n=1400, r=0.12, t=3, c=32, dt="f32"),        # split-bf16 rows kernel, 16x16x4 weight kernel
+    dict(n=1200, r=0.12, t=3, c=64, dt="bf16"),
+    dict(n=900, r=0.16, t=5, c=256, dt="bf16"),       # wide kernels
+])
+def test_determinism_matrix_core_paths(pcpp, case):
+    """The tuned kernels add partial results in a fixed order: two runs give identical bits."""
+    rng = np.random.default_rng(case["n"])
+    p = rng.uniform(0, 1, (case["n"], 3)).astype(np.float32)
+    K, c = case["t"] ** 3, case["c"]
+    dt = torch.bfloat16 if case["dt"] == "bf16" else torch.float32
+    x = dev(rng.standard_normal((case["n"], c)).astype(np.float32), dt)
+    w = dev((rng.standard_normal((K, c, c)) / np.sqrt(K * c)).astype(np.float32), dt)
+    dy = dev(rng.standard_normal((case["n"], c)).astype(np.float32), dt)
+    runs = []
+    for _ in range(2):
+        T = build_gpu(pcpp, p, p, case["r"], case["t"], same=True)
+        runs.append([pcpp.pcpp_mvmr_fwd(x, w, T).cpu().numpy(), pcpp.pcpp_mvmr_bwd_input(dy, w, T).cpu().numpy(),
+                     pcpp.pcpp_mvmr_bwd_weight(x, dy, T).cpu().numpy()])
+    for a, b in zip(*runs):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("c", [64, 256])
+def test_bf16_outputs(pcpp, c):
+    """out / dx emitted as bf16: the fp32 result rounded once (tolerance of the bf16 inputs plus one rounding)."""
+    rng = np.random.default_rng(c)
+    n, r, t = 1100, 0.15, 3
+    p = rng.uniform(0, 1, (n, 3)).astype(np.float32)
+    K = t ** 3
+    x = scenes.round_to_bf16(rng.standard_normal((n, c)).astype(np.float32))
+    w = scenes.round_to_bf16((rng.standard_normal((K, c, c)) / np.sqrt(K * c)).astype(np.float32))
+    dy = scenes.round_to_bf16(rng.standard_normal((n, c)).astype(np.float32))
+    o, i, k, seg = oracle.build_triplets(p, p, np.float32(r), t)
+    T = build_gpu(pcpp, p, p, r, t, same=True)
+    check_triplets(T, o, i, k, seg)
+    bf = torch.bfloat16
+    out = pcpp.pcpp_mvmr_fwd(dev(x, bf), dev(w, bf), T, out_dtype=bf)
+    assert out.dtype == bf
+    ref, scale = oracle_fwd(x, w, o, i, k, n)
+    assert_close(out.float().cpu().numpy(), ref, scale, TOL["bf16"] + 2.0 ** -8, f"bf16 out c={c}")
+    gx = pcpp.pcpp_mvmr_bwd_input(dev(dy, bf), dev(w, bf), T, out_dtype=bf)
+    assert gx.dtype == bf
+    ref, scale = oracle_bwd_input(dy, w, o, i, k, n)
+    assert_close(gx.float().cpu().numpy(), ref, scale, TOL["bf16"] + 2.0 ** -8, f"bf16 dx c={c}")
+
+
+def test_wide_layer_long_lists(pcpp):
+    """256 -> 256 with hundreds of triplets per (cell, 32-centre block): the wide kernel's path for lists longer
+    than its prefetch ring, and runs that straddle its 64-triplet groups."""
+    rng = np.random.default_rng(21)
+    p = np.concatenate([rng.normal(0.5, 0.03, (500, 3)), rng.uniform(0, 1, (300, 3))]).astype(np.float32)
+    r, t, c = 0.12, 3, 256
+    K = t ** 3
+    x = scenes.round_to_bf16(rng.standard_normal((len(p), c)).astype(np.float32))
+    w = scenes.round_to_bf16((rng.standard_normal((K, c, c)) / np.sqrt(K * c)).astype(np.float32))
+    dy = scenes.round_to_bf16(rng.standard_normal((len(p), c)).astype(np.float32))
+    s = scenes.Scene(0, "dense256", p, p, float(np.float32(r)), t, c, c, "bf16")
+    o, i, k, seg = oracle.build_triplets(p, p, s.radius, t)
+    per_block_cell = np.bincount(k.astype(np.int64) * (len(p) // 32 + 1) + o // 32)
+    assert per_block_cell.max() > 256
+    T = build_gpu(pcpp, p, p, r, t, same=True)
+    check_triplets(T, o, i, k, seg)
+    run_ops(pcpp, s, T, x, w, dy, o, i, k, ("fwd", "bwd_input", "bwd_weight"))
