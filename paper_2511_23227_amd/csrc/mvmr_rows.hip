@@ -99,11 +99,11 @@ __global__ void pack_w_split_kernel(const float *__restrict__ w, uint16_t *__res
     }
 }
 
-// Waves per SIMD the register allocation must leave room for: these two layers are bound by memory latency
-// and sit just above a register-count step without this.
+// Waves per SIMD the register allocation must leave room for: these layers are bound by memory latency and sit
+// just above a register-count step without this (measured per shape; 128 -> 64 is better left alone).
 constexpr int rows_min_waves(bool bf16, int c_src, int c_dst)
 {
-    return (!bf16 && c_src == 32 && c_dst == 32) ? 4 : ((bf16 && c_src == 64 && c_dst == 64) ? 3 : 1);
+    return (!bf16 && c_src == 32 && c_dst == 32) ? 4 : ((bf16 && c_src == 64 && c_dst == 64) ? 3 : ((bf16 && c_src == 64 && c_dst == 128) ? 2 : 1));
 }
 
 template <bool BF16, int C_SRC, int C_DST, int NW, typename TOut>
