@@ -45,15 +45,18 @@ __device__ inline unsigned long long pack_key(int cx, int cy, int cz)
 
 // ---- hashed grid over the candidate set ------------------------------------------------------
 
-// empty table: no keys, zero populations (slots + 1 entries, the input of the prefix sum), zero cursors
+// empty table: no keys, zero populations (slots + 1 entries, the input of the prefix sum), zero cursors;
+// the first call of a build also zeroes the status words of all its prefix sums
 __global__ __launch_bounds__(256) void grid_clear(unsigned long long *__restrict__ keys, uint32_t *__restrict__ cnt,
-                                                  uint32_t *__restrict__ cursor, int64_t slots)
+                                                  uint32_t *__restrict__ cursor, int64_t slots,
+                                                  unsigned long long *__restrict__ scan_status, int64_t scan_words)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i <= slots; i += stride) {
         cnt[i] = 0u;
         if (i < slots) { keys[i] = EMPTY_KEY; cursor[i] = 0u; }
     }
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < scan_words; i += stride) scan_status[i] = 0ull;
 }
 
 __global__ __launch_bounds__(256) void grid_insert(const float *__restrict__ xyz, int64_t n, double inv_g,
@@ -311,12 +314,15 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                                                              int32_t *__restrict__ out_k,
                                                              uint32_t *__restrict__ run_start_out, int list_cap,
                                                              const uint32_t *__restrict__ hits, uint32_t hit_stride,
-                                                             uint32_t out_cap)
+                                                             uint32_t out_cap, int64_t *__restrict__ seg_out)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
     __shared__ uint32_t list_all[SEARCH_WAVES][LIST_CAP_MAX];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
+    // start of every cell's segment (Sec. 3.3.2): the offset of its first tile; entry K is |T|
+    if (seg_out && tile == 0)
+        for (int k = threadIdx.x; k <= K; k += SEARCH_THREADS) seg_out[k] = (int64_t)tile_ptr[(size_t)k * n_tiles];
     const uint32_t *cnt_tile = tile_cnt + (size_t)tile * K * TILE;
     for (int idx = threadIdx.x; idx < K * TILE; idx += SEARCH_THREADS) tbl[idx] = cnt_tile[idx];
     __syncthreads();
@@ -513,13 +519,6 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
     }
 }
 
-__global__ void seg_offsets_kernel(const uint32_t *__restrict__ tile_ptr, int K, int64_t n_tiles,
-                                   int64_t *__restrict__ seg_offsets)
-{
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k <= K) seg_offsets[k] = (int64_t)tile_ptr[(size_t)k * n_tiles];
-}
-
 // ---- host side ------------------------------------------------------------------------------
 
 struct GridScratch {
@@ -548,10 +547,12 @@ GridScratch grid_scratch(size_t base, int64_t n)
     return s;
 }
 
+constexpr int N_SCANS = 4;           // prefix sums of one build, each with status words of its own
+
 struct BuildScratch {
     GridScratch grid_in, grid_out;
-    size_t scan_off;                 // scratch of the prefix sums
-    size_t total_off;                // unsigned long long[2]
+    size_t scan_off;                 // status words of the prefix sums: N_SCANS regions of scan_stride bytes
+    size_t scan_stride;
     size_t fwd_ptr_off, fwd_cnt_off; // used when the caller gives no plan
     size_t bwd_ptr_off, bwd_cnt_off;
     size_t end;                      // without hit lists
@@ -581,8 +582,8 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity 
     int64_t scan_n = b.grid_in.slots > b.grid_out.slots ? b.grid_in.slots : b.grid_out.slots;
     if ((int64_t)K * nt_o > scan_n) scan_n = (int64_t)K * nt_o;
     if ((int64_t)K * nt_i > scan_n) scan_n = (int64_t)K * nt_i;
-    b.scan_off = off;    off += scan_scratch_bytes(scan_n);
-    b.total_off = off;   off += 256;
+    b.scan_stride = scan_scratch_bytes(scan_n);
+    b.scan_off = off;    off += N_SCANS * b.scan_stride;
     b.fwd_ptr_off = off; off += align_up((size_t)(K * nt_o + 1) * 4);
     b.fwd_cnt_off = off; off += align_up((size_t)(nt_o > 0 ? nt_o : 1) * K * TILE * 4);
     b.bwd_ptr_off = off; off += align_up((size_t)(K * nt_i + 1) * 4);
@@ -600,8 +601,10 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity 
     return b;
 }
 
+// scan_scratch: the status words of this grid's prefix sum; clear_words > 0: the status words of all the
+// build's prefix sums start at scan_scratch and are zeroed here
 int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridScratch &gs, void *scan_scratch,
-               GridView *view, hipStream_t stream)
+               int64_t clear_words, GridView *view, hipStream_t stream)
 {
     auto *keys = reinterpret_cast<unsigned long long *>(ws + gs.keys_off);
     auto *cnt = reinterpret_cast<uint32_t *>(ws + gs.cnt_off);
@@ -612,7 +615,8 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
     {
         int64_t blocks = ceil_div(gs.slots + 1, 256);
         if (blocks > 4096) blocks = 4096;
-        grid_clear<<<(unsigned)blocks, 256, 0, stream>>>(keys, cnt, cursor, gs.slots);
+        grid_clear<<<(unsigned)blocks, 256, 0, stream>>>(keys, cnt, cursor, gs.slots,
+                                                         static_cast<unsigned long long *>(scan_scratch), clear_words);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if (n > 0) {
@@ -755,8 +759,8 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     const bool keep_hits = bs.fwd_stride != 0 && workspace_bytes >= bs.end_with_hits;
     uint32_t *f_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.fwd_hits_off) : nullptr;
     uint32_t *b_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.bwd_hits_off) : nullptr;
-    void *scan_scratch = ws + bs.scan_off;
-    auto *total_dev = reinterpret_cast<unsigned long long *>(ws + bs.total_off);
+    // one set of status words per prefix sum: candidates' grid, forward counts, centres' grid, swapped counts
+    auto scan_scratch = [&](int which) -> void * { return ws + bs.scan_off + (size_t)which * bs.scan_stride; };
 
     // grid pitch a hair above r so that, with the binary64 cell computation, any accepted pair lies
     // in adjacent grid cells (27-cell stencil is conservative)
@@ -770,7 +774,8 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
 
     int rc;
     GridView grid_in;
-    if ((rc = build_grid(in_xyz, n_in, inv_g, ws, bs.grid_in, scan_scratch, &grid_in, stream)) != PCPP_OK) return rc;
+    if ((rc = build_grid(in_xyz, n_in, inv_g, ws, bs.grid_in, scan_scratch(0),
+                         (int64_t)(N_SCANS * bs.scan_stride / sizeof(unsigned long long)), &grid_in, stream)) != PCPP_OK) return rc;
 
     const int64_t nt_o = ceil_div(n_out, TILE);
     const size_t lds = (size_t)K * TILE * sizeof(uint32_t);
@@ -807,16 +812,25 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
                 out_xyz, n_out, grid_in, q, K, nt_o, fwd_out, CountOut{nullptr, nullptr, nullptr}, bs.fwd_stride);
         PCPP_HIP_CHECK(hipGetLastError());
     }
-    if ((rc = scan_exclusive_u32(f_ptr, f_ptr, (int64_t)K * nt_o, scan_scratch, total_dev, stream)) != PCPP_OK) return rc;
+    // the offsets inside the plan do not depend on |T| (the only array that does comes last)
+    const PlanLayout pl = (plan && !count_only) ? plan_layout(n_in, n_out, K, 0, plan_flags) : PlanLayout{};
+    if (plan && !count_only && plan_bytes < pl.bytes) {
+        set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs at least %zu", plan_bytes, pl.bytes);
+        return PCPP_ERR_WORKSPACE;
+    }
+    char *pb = static_cast<char *>(plan);
+    // the tile offsets go straight into the plan when one is wanted
+    uint32_t *f_off = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.tile_ptr_off) : f_ptr;
 
-    // |T| travels to pinned host memory behind an event, so that the host can pick it up while the second
-    // pass is already running; that pass guards its writes with the capacities instead of waiting for the check.
+    // |T| is written by the prefix sum into pinned host memory, with an event behind it, so that the host can
+    // pick it up while the second pass is already running; that pass guards its writes with the capacities
+    // instead of waiting for the check.
     HostTotal &ht = host_total();
     if (!ht.pinned) {
         PCPP_HIP_CHECK(hipHostMalloc(reinterpret_cast<void **>(&ht.pinned), 64, hipHostMallocDefault));
         PCPP_HIP_CHECK(hipEventCreateWithFlags(&ht.ready, hipEventDisableTiming));
     }
-    PCPP_HIP_CHECK(hipMemcpyAsync(ht.pinned, total_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, stream));
+    if ((rc = scan_exclusive_u32(f_ptr, f_off, (int64_t)K * nt_o, scan_scratch(1), ht.pinned, stream)) != PCPP_OK) return rc;
     PCPP_HIP_CHECK(hipEventRecord(ht.ready, stream));
     auto wait_total = [&](unsigned long long &total) -> int {
         PCPP_HIP_CHECK(hipEventSynchronize(ht.ready));
@@ -831,31 +845,17 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     unsigned long long total = 0;
     if (count_only) return wait_total(total);
 
-    // the offsets inside the plan do not depend on |T| (the only array that does comes last)
-    const PlanLayout pl = plan ? plan_layout(n_in, n_out, K, 0, plan_flags) : PlanLayout{};
-    if (plan && plan_bytes < pl.bytes) {
-        set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs at least %zu", plan_bytes, pl.bytes);
-        return PCPP_ERR_WORKSPACE;
-    }
     const uint32_t tri_cap = (uint32_t)(capacity < (int64_t)INT32_MAX ? capacity : (int64_t)INT32_MAX);
-    char *pb = static_cast<char *>(plan);
     if (nt_o > 0) {
         uint32_t *f_runs = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
         query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
-                                                                        f_ptr, tri_o, tri_i, tri_k, f_runs,
-                                                                        g_list_cap, f_hits, bs.fwd_stride, tri_cap);
-        PCPP_HIP_CHECK(hipGetLastError());
-    }
-    if (nt_o > 0) {
-        seg_offsets_kernel<<<(K + 1 + 63) / 64, 64, 0, stream>>>(f_ptr, K, nt_o, seg_offsets);
+                                                                        f_off, tri_o, tri_i, tri_k, f_runs,
+                                                                        g_list_cap, f_hits, bs.fwd_stride, tri_cap,
+                                                                        seg_offsets);
         PCPP_HIP_CHECK(hipGetLastError());
     } else {
         // no outputs: every run starts at 0
         PCPP_HIP_CHECK(hipMemsetAsync(seg_offsets, 0, (size_t)(K + 1) * sizeof(int64_t), stream));
-    }
-    if (want_fwd_plan) {
-        PCPP_HIP_CHECK(hipMemcpyAsync(pb + pl.fwd.tile_ptr_off, f_ptr, (size_t)(K * nt_o + 1) * 4,
-                                      hipMemcpyDeviceToDevice, stream));
     }
     if (want_bwd_plan) {
         // input-gradient side: centres = inputs, candidates = outputs; same predicate with the roles
@@ -865,7 +865,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         if (out_xyz == in_xyz && n_out == n_in) {
             grid_out = grid_in;
         } else {
-            if ((rc = build_grid(out_xyz, n_out, inv_g, ws, bs.grid_out, scan_scratch, &grid_out, stream)) != PCPP_OK)
+            if ((rc = build_grid(out_xyz, n_out, inv_g, ws, bs.grid_out, scan_scratch(2), 0, &grid_out, stream)) != PCPP_OK)
                 return rc;
         }
         uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
@@ -879,12 +879,13 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
                 bs.bwd_stride);
             PCPP_HIP_CHECK(hipGetLastError());
         }
-        if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch, total_dev + 1, stream)) != PCPP_OK)
+        if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch(3), nullptr, stream)) != PCPP_OK)
             return rc;
         if (nt_i > 0) {
             query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
                                                                            b_ptr, nullptr, b_gather, nullptr, b_runs,
-                                                                           g_list_cap, b_hits, bs.bwd_stride, gather_cap);
+                                                                           g_list_cap, b_hits, bs.bwd_stride, gather_cap,
+                                                                           nullptr);
             PCPP_HIP_CHECK(hipGetLastError());
         }
     }

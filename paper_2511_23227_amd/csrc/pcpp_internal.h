@@ -64,8 +64,9 @@ struct PlanSideView {
 
 // ---- device-wide exclusive scan of uint32 (scan.hip) ------------------------------------------
 // out[i] = sum_{j<i} in[j] for i in [0, n]; out has n+1 entries (out may alias in when it has
-// room for n+1).  block_sums: scratch of scan_scratch_bytes(n).  total64 (device, optional)
-// receives the 64-bit total.
+// room for n+1).  scratch: scan_scratch_bytes(n) bytes that are all zero when the scan starts (it
+// leaves them non-zero: zero them again before the next scan, or give every scan its own).
+// total64 (device, optional) receives the 64-bit total.
 size_t scan_scratch_bytes(int64_t n);
 int scan_exclusive_u32(const uint32_t *in, uint32_t *out, int64_t n, void *scratch,
                        unsigned long long *total64, hipStream_t stream);

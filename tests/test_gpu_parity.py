@@ -355,3 +355,55 @@ def test_wide_layer_long_lists(pcpp):
     T = build_gpu(pcpp, p, p, r, t, same=True)
     check_triplets(T, o, i, k, seg)
     run_ops(pcpp, s, T, x, w, dy, o, i, k, ("fwd", "bwd_input", "bwd_weight"))
+
+
+RANDOM_SHAPES = [(32, 32, "f32"), (64, 64, "f32"), (16, 16, "f32"), (64, 64, "bf16"), (64, 128, "bf16"),
+                 (128, 64, "bf16"), (128, 128, "bf16"), (256, 256, "bf16"), (48, 24, "bf16")]
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_small_scenes(pcpp, seed):
+    """Seeded random draws of everything at once: kernel size 1..6, radius, point counts, uniform / clustered /
+    lattice-with-ties clouds, self-convolution or separate centres, and a channel shape from every kernel family.
+    Triplets bit-exact and all three ops within tolerance on every element, twelve cases per seed."""
+    rng = np.random.default_rng(seed)
+    for case in range(12):
+        t = int(rng.integers(1, 7))
+        n_in = int(rng.integers(1, 2500))
+        same = bool(rng.random() < 0.5)
+        n_out = n_in if same else int(rng.integers(1, 2500))
+        kind = int(rng.integers(0, 3))
+
+        def cloud(n):
+            if kind == 0:
+                return rng.uniform(0, 1, (n, 3))
+            if kind == 1:       # half the points in a blob far denser than the rest
+                return np.concatenate([rng.normal(0.5, 0.03, (n // 2, 3)), rng.uniform(0, 1, (n - n // 2, 3))])
+            return rng.integers(0, 24, (n, 3)) / 16.0      # many points exactly on the ball and on cell faces
+
+        pin = cloud(n_in).astype(np.float32)
+        pout = pin if same else cloud(n_out).astype(np.float32)
+        r = float(np.float32(rng.choice([0.0625, 0.1, 0.15, 0.25])))
+        cin, cout, dt = RANDOM_SHAPES[int(rng.integers(0, len(RANDOM_SHAPES)))]
+        what = f"seed {seed} case {case}: t={t} n_in={n_in} n_out={n_out} same={same} kind={kind} r={r} " \
+               f"{cin}->{cout} {dt}"
+        print(what, flush=True)
+        K = t ** 3
+        o, i, k, seg = oracle.build_triplets(pin, pout, np.float32(r), t)
+        T = build_gpu(pcpp, pin, pout, r, t, same=same)
+        check_triplets(T, o, i, k, seg)
+        x = rng.standard_normal((n_in, cin)).astype(np.float32)
+        w = (rng.standard_normal((K, cout, cin)) / np.sqrt(K * cin)).astype(np.float32)
+        dy = rng.standard_normal((n_out, cout)).astype(np.float32)
+        tdt = torch.float32
+        if dt == "bf16":
+            x, w, dy, tdt = scenes.round_to_bf16(x), scenes.round_to_bf16(w), scenes.round_to_bf16(dy), torch.bfloat16
+        out = pcpp.pcpp_mvmr_fwd(dev(x, tdt), dev(w, tdt), T).cpu().numpy()
+        ref, scale = oracle_fwd(x, w, o, i, k, n_out)
+        assert_close(out, ref, scale, TOL[dt], what + " fwd")
+        gx = pcpp.pcpp_mvmr_bwd_input(dev(dy, tdt), dev(w, tdt), T).cpu().numpy()
+        ref, scale = oracle_bwd_input(dy, w, o, i, k, n_in)
+        assert_close(gx, ref, scale, TOL[dt], what + " bwd_input")
+        gw = pcpp.pcpp_mvmr_bwd_weight(dev(x, tdt), dev(dy, tdt), T).cpu().numpy()
+        ref, scale = oracle_bwd_weight(x, dy, o, i, k, K)
+        assert_close(gw, ref, scale, TOL[dt], what + " bwd_weight")
