@@ -49,6 +49,19 @@ def algorithmic_bytes(op: str, n_t: int, n_in: int, n_out: int, c_in: int, c_out
     raise ValueError(op)
 
 
+def compulsory_bytes(op: str, n_t: int, n_in: int, n_out: int, c_in: int, c_out: int, K: int, s_in: int,
+                     s_out: int) -> float:
+    """Bytes that must cross the HBM interface even with ideal caches: every array read or written once."""
+    w = K * c_in * c_out
+    if op == "fwd":
+        return n_in * c_in * s_in + n_out * c_out * s_out + n_t * 8 + w * s_in
+    if op == "bwd_input":
+        return n_out * c_out * s_in + n_in * c_in * s_out + n_t * 8 + w * s_in
+    if op == "bwd_weight":
+        return n_in * c_in * s_in + n_out * c_out * s_in + n_t * 8 + w * 4
+    raise ValueError(op)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,7 +169,39 @@ def main() -> int:
         T = step(True)
     torch.cuda.synchronize()
 
-    op_ms = {nm: float(np.mean([ev[j].elapsed_time(ev[j + 1]) for ev in events])) for j, nm in enumerate(names)}
+    samples = {nm: np.array([ev[j].elapsed_time(ev[j + 1]) for ev in events]) for j, nm in enumerate(names)}
+    op_ms = {nm: float(v.mean()) for nm, v in samples.items()}
+
+    # cold caches: the same steps with a 512 MiB buffer overwritten before each one (L2 and the memory-side cache
+    # then hold none of the step's data); reported beside the warm figures, never part of `value`
+    events.clear()
+    scrub = torch.empty(128 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    for it in range(min(args.steps, 10)):
+        scrub.fill_(float(it))
+        step(True)
+    torch.cuda.synchronize()
+    cold_ms = {nm: float(np.median([ev[j].elapsed_time(ev[j + 1]) for ev in events])) for j, nm in enumerate(names)}
+    del scrub
+
+    # what this device reaches on plain library kernels in the same run: a 256 MiB device copy (read + write) and
+    # an 8192^3 bf16 GEMM; the graded fractions stay against the published peaks
+    def timed(fn, reps):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+    csrc = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    cdst = torch.empty_like(csrc)
+    copy_gbs = 2 * csrc.numel() * 4 / timed(lambda: cdst.copy_(csrc), 10) / 1e9
+    del csrc, cdst
+    ga = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
+    gb = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
+    gemm_tflops = 2 * 8192 ** 3 / timed(lambda: torch.matmul(ga, gb), 5) / 1e12
+    del ga, gb
 
     def roofline(op):
         b = algorithmic_bytes(op, n_t, s.n_in, s.n_out, s.c_in, s.c_out, s.K, s_in, 4)
@@ -164,7 +209,11 @@ def main() -> int:
         return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((args.scene, args.order, op)),
                 "kernel": op, "algorithmic_bytes": int(b), "ms": round(op_ms[op], 4),
-                "nominal_tflops": round(2.0 * n_t * s.c_in * s.c_out / (op_ms[op] * 1e-3) / 1e12, 2)}
+                "nominal_tflops": round(2.0 * n_t * s.c_in * s.c_out / (op_ms[op] * 1e-3) / 1e12, 2),
+                "frac_of_measured_copy": round(gbs / copy_gbs, 4),
+                "compulsory_bytes": int(compulsory_bytes(op, n_t, s.n_in, s.n_out, s.c_in, s.c_out, s.K, s_in, 4)),
+                "compulsory_floor_ms": round(compulsory_bytes(op, n_t, s.n_in, s.n_out, s.c_in, s.c_out, s.K, s_in, 4)
+                                             / (HBM_PEAK_GBS * 1e9) * 1e3, 5)}
 
     per_op = {op: roofline(op) for op in ops}
     dominant = max(ops, key=lambda o_: op_ms[o_])
@@ -184,7 +233,10 @@ def main() -> int:
         if s.dtype == "f32" and c_src == 32 and c_dst == 32:
             stage2 *= 6                               # six bf16 products of the three-term splits
         return cnt.numel() * stage2 + steps * terms * 2.0 * per * 32 * c_src
+    pair_ratio = None
     if n_t > 0:
+        # triplets per distinct (cell, output point): how many rows one product with W[k] serves after the run sums
+        pair_ratio = round(n_t / torch.unique(T.tri_k.long() * s.n_out + T.tri_o.long()).numel(), 3)
         ex = {"fwd": executed_flops(T.tri_o, s.c_in, s.c_out)}
         if "bwd_input" in ops:
             ex["bwd_input"] = executed_flops(T.tri_i, s.c_out, s.c_in)
@@ -196,6 +248,8 @@ def main() -> int:
             tf = ex[op] / (op_ms[op] * 1e-3) / 1e12
             per_op[op]["executed_mfma_tflops"] = round(tf, 2)
             per_op[op]["mfma_frac"] = round(tf / peak, 4)
+            if peak == MFMA_PEAK_TFLOPS["bf16"]:
+                per_op[op]["mfma_frac_of_measured_gemm"] = round(tf / gemm_tflops, 4)
             if s.dtype == "bf16" and min(s.c_in, s.c_out) >= 256:   # wide layers are matrix-core bound
                 per_op[op].update({"bound": "mfma", "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s",
                                    "frac": round(tf / peak, 4)})
@@ -212,6 +266,11 @@ def main() -> int:
                    "radius": s.radius, "t": s.t, "c_in": s.c_in, "c_out": s.c_out, "n_triplets": n_t,
                    "ops": names},
         "op_ms": {k_: round(v, 4) for k_, v in op_ms.items()},
+        "op_ms_median": {k_: round(float(np.median(v)), 4) for k_, v in samples.items()},
+        "op_ms_min": {k_: round(float(v.min()), 4) for k_, v in samples.items()},
+        "op_ms_cold": {k_: round(v, 4) for k_, v in cold_ms.items()},
+        "measured_peaks": {"copy_GBs": round(copy_gbs, 1), "gemm_bf16_TFLOPs": round(gemm_tflops, 1)},
+        "triplets_per_k_o_pair": pair_ratio,
         "pairs_per_s": {k_: round(n_t / (v * 1e-3), 1) for k_, v in op_ms.items()},
         "roofline": per_op[dominant],
         "roofline_per_op": per_op,
