@@ -350,6 +350,170 @@ __global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__r
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 256 -> 256: one block of eight waves per chunk, wave w owning the 128 x 64 sub-block (output channels
+// 128 (w / 4) .., input channels 64 (w % 4) ..) of dW[k].  With 128 accumulator registers a wave has no room
+// to keep a second batch of rows in flight, and two waves per SIMD hide little of a gather's latency.  Here
+// the block fetches every row of a batch of 32 triplets once (x[i] and dy[o]: 32 x 1 KB, 64 bytes per thread)
+// and passes it through LDS, so the rows are four batches deep in flight at a fixed cost of registers:
+//   step s:  request the indices of batch s + 4 | request the rows of batch s + 2 (indices asked for two steps
+//            ago) | multiply batch s out of LDS buffer s % 2 | store the rows of batch s + 1 (asked for one
+//            step ago) into buffer (s + 1) % 2 | barrier
+// A batch never crosses the end of a cell's run; rows past its end are stored as zeros.  The operands are read
+// from LDS in the layout weight_wide_kernel reads from memory.  Thread (row r = tid / 16, h = (tid / 8) % 2,
+// q = tid % 8) moves bytes 128 j + 16 q .. + 15 (j = 0..3) of x[i_r] (h = 0) or dy[o_r] (h = 1).
+// ---------------------------------------------------------------------------------------------
+constexpr int LDS_WAVES = 8;
+constexpr int LDS_BATCH_BYTES = 32 * 1024;        // 32 rows of x (512 B) then 32 rows of dy (512 B)
+
+struct Batch {
+    int64_t b0;     // first triplet
+    int n;          // triplets (0: no batch)
+    int k;          // cell
+    bool last;      // the run (or the chunk) ends with this batch
+};
+
+__global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uint16_t *__restrict__ x,
+                                                                        const uint16_t *__restrict__ dy,
+                                                                        float *__restrict__ part,
+                                                                        const int32_t *__restrict__ tri_o,
+                                                                        const int32_t *__restrict__ tri_i,
+                                                                        const int64_t *__restrict__ seg, int K,
+                                                                        int64_t n_triplets, int chunk, int64_t n_chunks)
+{
+    constexpr int C = 256, ROW = C * 2, X_OFF = 0, DY_OFF = 32 * ROW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char stage[];        // two batches
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int ci0 = (wave & 3) * 64, co0 = (wave >> 2) * 128;
+    const int64_t chunk_id = blockIdx.x;
+    int64_t p = chunk_id * chunk;
+    int64_t p_end = p + chunk;
+    if (p_end > n_triplets) p_end = n_triplets;
+
+    // cell of the first triplet: the k with seg[k] <= p < seg[k+1]
+    int k = 0;
+    for (int kb = 0; kb < K; kb += 64) {
+        const int kk = kb + lane;
+        const bool hit = kk < K && seg[kk] <= p && p < seg[kk + 1];
+        const unsigned long long msk = __ballot(hit);
+        if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
+    }
+    k = __builtin_amdgcn_readfirstlane(k);
+    auto next_batch = [&]() -> Batch {
+        while (p < p_end) {
+            int64_t q_end = seg[k + 1];
+            if (q_end > p_end) q_end = p_end;
+            if (q_end <= p) { ++k; continue; }       // empty run
+            Batch b;
+            b.b0 = p;
+            b.n = (int)(q_end - p < 32 ? q_end - p : 32);
+            b.k = k;
+            p += b.n;
+            b.last = p == q_end;
+            if (b.last) ++k;
+            return b;
+        }
+        return Batch{0, 0, 0, false};
+    };
+
+    // mover role of this thread
+    const int r = tid >> 4, h = (tid >> 3) & 1, q = tid & 7;
+    const int32_t *tri_mine = h ? tri_o : tri_i;
+    const unsigned char *rows_mine = reinterpret_cast<const unsigned char *>(h ? dy : x);
+    const int lds_mine = (h ? DY_OFF : X_OFF) + r * ROW + q * 16;
+
+    Batch b0 = Batch{0, 0, 0, false}, b1 = b0, b2 = b0, b3 = b0, b4 = next_batch();
+    int32_t idx2 = 0, idx3 = 0, idx4 = 0;       // row index of this thread in batches s + 2, s + 3, s + 4
+    v4u rows1[4], rows2[4];                      // this thread's 64 bytes of batches s + 1 and s + 2
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rows1[j] = rows2[j] = v4u{0u, 0u, 0u, 0u};
+
+    v4f acc[2][4][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) acc[a][b][d] = v4f{0.f, 0.f, 0.f, 0.f};
+    bool first = true;
+    int s = 0;
+    while (b0.n | b1.n | b2.n | b3.n | b4.n) {
+        // indices of batch s + 4
+        idx4 = (b4.n > r) ? tri_mine[b4.b0 + r] : 0;
+        // rows of batch s + 2
+        {
+            const unsigned char *src = rows_mine + (size_t)idx2 * ROW + q * 16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                rows2[j] = (b2.n > r) ? *reinterpret_cast<const v4u *>(src + j * 128) : v4u{0u, 0u, 0u, 0u};
+        }
+        // batch s out of LDS
+        if (b0.n) {
+            const unsigned char *buf = stage + (s & 1) * LDS_BATCH_BYTES;
+            v2u xw[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                xw[e] = *reinterpret_cast<const v2u *>(buf + X_OFF + (8 * g + e) * ROW + (ci0 + 4 * m) * 2);
+            v4u bv[4];
+#pragma unroll
+            for (int qs = 0; qs < 4; ++qs)
+#pragma unroll
+                for (int wd = 0; wd < 4; ++wd)
+                    bv[qs][wd] = __builtin_amdgcn_perm(xw[2 * wd + 1][qs >> 1], xw[2 * wd][qs >> 1],
+                                                       (qs & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+            for (int qo = 0; qo < 2; ++qo) {
+                v2u dyw[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    dyw[e] = *reinterpret_cast<const v2u *>(buf + DY_OFF + (8 * g + e) * ROW + (co0 + 64 * qo + 4 * m) * 2);
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    v4u av;
+#pragma unroll
+                    for (int wd = 0; wd < 4; ++wd)
+                        av[wd] = __builtin_amdgcn_perm(dyw[2 * wd + 1][qd >> 1], dyw[2 * wd][qd >> 1],
+                                                       (qd & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+                    for (int qs = 0; qs < 4; ++qs)
+                        acc[qo][qd][qs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv[qs]), acc[qo][qd][qs], 0, 0, 0);
+                }
+            }
+            if (b0.last) {
+                // flush: lane (m, g), register j of acc[qo][qd][qs] is dW[co0 + 64 qo + 4 (4g + j) + qd][ci0 + 4m + qs]
+                float *dstp = part + (size_t)(first ? chunk_id : n_chunks + b0.k) * C * C;
+#pragma unroll
+                for (int qo = 0; qo < 2; ++qo)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int co = co0 + 64 * qo + 4 * (4 * g + j) + qd;
+                            const int ci = ci0 + 4 * m;
+                            *reinterpret_cast<v4f *>(dstp + (size_t)co * C + ci) =
+                                v4f{acc[qo][qd][0][j], acc[qo][qd][1][j], acc[qo][qd][2][j], acc[qo][qd][3][j]};
+                            acc[qo][qd][0][j] = acc[qo][qd][1][j] = acc[qo][qd][2][j] = acc[qo][qd][3][j] = 0.f;
+                        }
+                first = false;
+            }
+        }
+        // rows of batch s + 1 into the other buffer (its readers passed the previous barrier)
+        if (b1.n) {
+            unsigned char *dst = stage + ((s + 1) & 1) * LDS_BATCH_BYTES + lds_mine;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<v4u *>(dst + j * 128) = rows1[j];
+        }
+        __syncthreads();
+        b0 = b1; b1 = b2; b2 = b3; b3 = b4; b4 = next_batch();
+        idx2 = idx3; idx3 = idx4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rows1[j] = rows2[j];
+        ++s;
+    }
+}
+
 // dw[k][e] = (partial of the run's head, if it starts inside a chunk) + partials of the chunks whose first
 // triplet lies in run k.  16 threads share one element: thread g adds chunks c0+g, c0+g+16, ... in
 // ascending order and the 16 sums are then added in order of g, so the result is reproducible.
@@ -403,7 +567,15 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     }
     float *part = static_cast<float *>(workspace);
     if (n_chunks > 0) {
-        if constexpr (!BF16 && SUB_IN == C_IN && SUB_OUT == C_OUT)
+        // 16-byte row reads: rows are 512 bytes, so it is the two base addresses that decide
+        const bool rows_aligned = ((reinterpret_cast<uintptr_t>(a.feat) | reinterpret_cast<uintptr_t>(a.dense)) & 15) == 0;
+        if (BF16 && C_IN == 256 && C_OUT == 256 && rows_aligned) {
+            PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&weight_lds_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * LDS_BATCH_BYTES));
+            weight_lds_kernel<<<(unsigned)n_chunks, LDS_WAVES * 64, 2 * LDS_BATCH_BYTES, stream>>>(
+                static_cast<const uint16_t *>(a.feat), static_cast<const uint16_t *>(a.dense), part, tri_o, a.gather, seg,
+                a.K, a.n_triplets, chunk, n_chunks);
+        } else if constexpr (!BF16 && SUB_IN == C_IN && SUB_OUT == C_OUT)
             weight_f32_kernel<C_IN, C_OUT><<<(unsigned)ceil_div(n_chunks, WAVES), WAVES * 64, 0, stream>>>(
                 static_cast<const float *>(a.feat), static_cast<const float *>(a.dense), part, tri_o, a.gather, seg, a.K,
                 a.n_triplets, chunk, n_chunks);
