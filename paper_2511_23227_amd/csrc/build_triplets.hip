@@ -798,8 +798,17 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     uint32_t *f_ptr = reinterpret_cast<uint32_t *>(ws + bs.fwd_ptr_off);
     uint32_t *f_cnt = reinterpret_cast<uint32_t *>(ws + bs.fwd_cnt_off);
     // A cloud queried against itself: one pass counts both sides (while two [K][64] tables fit beside the lists
-    // in the LDS share of two blocks per CU).
-    const bool one_pass = want_bwd_plan && out_xyz == in_xyz && n_out == n_in && 2 * lds <= (size_t)32 * 1024;
+    // in the LDS share of two blocks per CU, and within what one block may allocate on this device).
+    bool one_pass = want_bwd_plan && out_xyz == in_xyz && n_out == n_in && 2 * lds <= (size_t)72 * 1024;
+    if (one_pass && 2 * lds > (size_t)32 * 1024) {
+        int dev = 0, per_block = 0;
+        PCPP_HIP_CHECK(hipGetDevice(&dev));
+        PCPP_HIP_CHECK(hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+        if (2 * lds + (size_t)8 * 1024 > (size_t)per_block) one_pass = false;
+        else
+            PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false, true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * lds)));
+    }
     uint32_t *b_cnt = reinterpret_cast<uint32_t *>(ws + bs.bwd_cnt_off);
     uint32_t *b_sum = reinterpret_cast<uint32_t *>(ws + bs.bwd_ptr_off);   // per-(k, tile) sums of the swapped side
     if (nt_o > 0) {

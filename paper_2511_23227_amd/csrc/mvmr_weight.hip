@@ -5,6 +5,8 @@
 // added in a fixed order by a second kernel: no atomics, reproducible.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "pcpp_internal.h"
 
 namespace pcpp {
@@ -424,10 +426,13 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
     const int lds_mine = (h ? DY_OFF : X_OFF) + r * ROW + q * 16;
 
     Batch b0 = Batch{0, 0, 0, false}, b1 = b0, b2 = b0, b3 = b0, b4 = next_batch();
-    int32_t idx2 = 0, idx3 = 0, idx4 = 0;       // row index of this thread in batches s + 2, s + 3, s + 4
-    v4u rows1[4], rows2[4];                      // this thread's 64 bytes of batches s + 1 and s + 2
+    // Registers that a load is still filling are never copied (a copy would wait for the load): the two sets
+    // of row registers and the two index registers swap roles from one step to the next instead, with the step
+    // written once for each parity.
+    int32_t idx[2] = {0, 0};                     // row index of this thread in batch s + 2 (then s + 4): idx[s % 2]
+    v4u rows[2][4];                              // this thread's 64 bytes of batch s + 2: rows[s % 2]; s + 1: the other
 #pragma unroll
-    for (int j = 0; j < 4; ++j) rows1[j] = rows2[j] = v4u{0u, 0u, 0u, 0u};
+    for (int j = 0; j < 4; ++j) rows[0][j] = rows[1][j] = v4u{0u, 0u, 0u, 0u};
 
     v4f acc[2][4][4];
 #pragma unroll
@@ -437,20 +442,24 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
 #pragma unroll
             for (int d = 0; d < 4; ++d) acc[a][b][d] = v4f{0.f, 0.f, 0.f, 0.f};
     bool first = true;
-    int s = 0;
-    while (b0.n | b1.n | b2.n | b3.n | b4.n) {
-        // indices of batch s + 4
-        idx4 = (b4.n > r) ? tri_mine[b4.b0 + r] : 0;
-        // rows of batch s + 2
+
+    auto step = [&](auto parity) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(parity)::value;
+        // rows of batch s + 2 (index asked for two steps ago), then the index of batch s + 4 into the same register
+        // (both unconditional, so that the waits can be counted exactly: past a batch's end the index read is
+        // clamped to the last triplet and the row it names is fetched and then stored as zeros)
         {
-            const unsigned char *src = rows_mine + (size_t)idx2 * ROW + q * 16;
+            const unsigned char *src = rows_mine + (size_t)idx[PAR] * ROW + q * 16;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                rows2[j] = (b2.n > r) ? *reinterpret_cast<const v4u *>(src + j * 128) : v4u{0u, 0u, 0u, 0u};
+            for (int j = 0; j < 4; ++j) rows[PAR][j] = *reinterpret_cast<const v4u *>(src + j * 128);
+        }
+        {
+            const int64_t t = b4.b0 + r;
+            idx[PAR] = tri_mine[t < n_triplets ? t : n_triplets - 1];
         }
         // batch s out of LDS
         if (b0.n) {
-            const unsigned char *buf = stage + (s & 1) * LDS_BATCH_BYTES;
+            const unsigned char *buf = stage + PAR * LDS_BATCH_BYTES;
             v2u xw[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -499,18 +508,21 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
                 first = false;
             }
         }
-        // rows of batch s + 1 into the other buffer (its readers passed the previous barrier)
-        if (b1.n) {
-            unsigned char *dst = stage + ((s + 1) & 1) * LDS_BATCH_BYTES + lds_mine;
+        // rows of batch s + 1 (asked for one step ago) into the other buffer: its readers passed the last barrier
+        {
+            unsigned char *dst = stage + (PAR ^ 1) * LDS_BATCH_BYTES + lds_mine;
+            const bool keep = b1.n > r;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) *reinterpret_cast<v4u *>(dst + j * 128) = rows1[j];
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<v4u *>(dst + j * 128) = keep ? rows[PAR ^ 1][j] : v4u{0u, 0u, 0u, 0u};
         }
         __syncthreads();
         b0 = b1; b1 = b2; b2 = b3; b3 = b4; b4 = next_batch();
-        idx2 = idx3; idx3 = idx4;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) rows1[j] = rows2[j];
-        ++s;
+    };
+    while (b0.n | b1.n | b2.n | b3.n | b4.n) {
+        step(std::integral_constant<int, 0>{});
+        if (!(b0.n | b1.n | b2.n | b3.n | b4.n)) break;
+        step(std::integral_constant<int, 1>{});
     }
 }
 
