@@ -402,18 +402,21 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
         if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
     }
     k = __builtin_amdgcn_readfirstlane(k);
+    // run_end: end of cell k's run inside the chunk, read from seg only when the cell changes
+    int64_t run_end = seg[k + 1] < p_end ? seg[k + 1] : p_end;
     auto next_batch = [&]() -> Batch {
         while (p < p_end) {
-            int64_t q_end = seg[k + 1];
-            if (q_end > p_end) q_end = p_end;
-            if (q_end <= p) { ++k; continue; }       // empty run
+            if (run_end <= p) {                       // next cell (empty runs are passed over)
+                ++k;
+                run_end = seg[k + 1] < p_end ? seg[k + 1] : p_end;
+                continue;
+            }
             Batch b;
             b.b0 = p;
-            b.n = (int)(q_end - p < 32 ? q_end - p : 32);
+            b.n = (int)(run_end - p < 32 ? run_end - p : 32);
             b.k = k;
             p += b.n;
-            b.last = p == q_end;
-            if (b.last) ++k;
+            b.last = p == run_end;
             return b;
         }
         return Batch{0, 0, 0, false};
