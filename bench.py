@@ -26,12 +26,12 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
 # (scene, order, op); absent entries are reported as null.
 MEASURED_TRAFFIC: dict = {
-    (2, "default", "fwd"): int(290.0e6 + 16.0e6),         # rows_kernel: scaled FETCH_SIZE + WRITE_SIZE
-    (2, "default", "bwd_input"): int(290.0e6 + 16.0e6),
+    (2, "default", "fwd"): int(289.4e6 + 16.0e6),         # rows_kernel: scaled FETCH_SIZE + WRITE_SIZE
+    (2, "default", "bwd_input"): int(289.4e6 + 16.0e6),
     (2, "default", "bwd_weight"): int(390.6e6 + 19.8e6),  # weight_f32_kernel (weight_reduce adds 39.7e6 read)
-    (5, "default", "fwd"): int(27630e6 + 1024e6),         # rows_wide_kernel
-    (5, "default", "bwd_input"): int(27630e6 + 1024e6),
-    (5, "default", "bwd_weight"): int(42049e6 + 543e6),   # weight_wide_kernel
+    (5, "default", "fwd"): int(27531e6 + 1024e6),         # rows_wide_kernel
+    (5, "default", "bwd_input"): int(27531e6 + 1024e6),
+    (5, "default", "bwd_weight"): int(25409e6 + 543e6),   # weight_lds_kernel (weight_reduce adds 1086e6 read)
 }
 
 
