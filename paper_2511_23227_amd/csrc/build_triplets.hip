@@ -354,6 +354,45 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
         for (int d = 32; d >= 1; d >>= 1) nn += __shfl_xor(nn, d, 64);
         n_of[u] = nn;
     }
+    // Two centres at a time, one per half wave, while both of their kept lists fit 32 lanes (most do: the all-pairs
+    // ranking then costs one pass for the two).  Centres done here are marked by a zero count.
+    if (reuse_max >= 32 && list_cap >= 64) {
+        const int half = lane >> 5, l = lane & 31;
+#pragma unroll
+        for (int u = 0; u + 1 < PER_WAVE; u += 2) {
+            const uint32_t n0 = n_of[u], n1 = n_of[u + 1];
+            if (n0 == 0 || n1 == 0 || n0 > 32 || n1 > 32) continue;       // wave-uniform
+            const int al = wave + (u + half) * SEARCH_WAVES;
+            const int64_t a = tile * TILE + al;                         // both exist: their counts are not zero
+            const uint32_t n = half ? n1 : n0, nmax = n0 > n1 ? n0 : n1;
+            const uint32_t key = l < (int)n ? hits[(size_t)a * hit_stride + l] : 0xffffffffu;   // padding ranks nobody
+            list[lane] = key;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const uint32_t kbase = key & ~HIT_INDEX_MASK, rel = key & HIT_INDEX_MASK;
+            const uint32_t *other = list + 32 * half;
+            uint32_t rank = 0;
+            for (uint32_t e2 = 0; e2 < nmax; e2 += 8) {                 // reads past nmax see padding or real keys of
+                uint32_t v[8];                                          // this half only up to n: entries >= n are padding
+#pragma unroll
+                for (int w = 0; w < 8; ++w) v[w] = other[e2 + w];
+#pragma unroll
+                for (int w = 0; w < 8; ++w) rank += (v[w] - kbase) < rel ? 1u : 0u;
+            }
+            if (l < (int)n) {
+                const int k = (int)(key >> HIT_INDEX_BITS);
+                const uint32_t pos = tbl[k * TILE + al] + rank;
+                if (pos < out_cap) {
+                    if (out_c) out_c[pos] = (int32_t)a;
+                    if (out_b) out_b[pos] = (int32_t)rel;
+                    if (out_k) out_k[pos] = k;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            n_of[u] = n_of[u + 1] = 0;
+        }
+    }
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
         const int al = wave + u * SEARCH_WAVES;
