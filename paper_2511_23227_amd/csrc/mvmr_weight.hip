@@ -248,14 +248,7 @@ __global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__r
     constexpr int N_SUB_IN = C_IN / SUB_IN, N_SUB = N_SUB_IN * (C_OUT / SUB_OUT);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
-    // Two blocks share a chunk when it has twice as many sub-blocks as a block has waves.  Consecutive blocks go
-    // to different XCDs (eight, round-robin), each with its own L2: blocks j and j + 8 take the two halves, so
-    // that the rows both halves read are fetched from HBM once.
-    int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
-    if constexpr (N_SUB == 2 * WAVES) {
-        const int64_t j = blockIdx.x;
-        gw = ((j >> 4) * 8 + (j & 7)) * N_SUB + ((j >> 3) & 1) * WAVES + wave;
-    }
+    const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
     const int64_t chunk_id = gw / N_SUB;
     const int sub = (int)(gw % N_SUB);
     const int ci0 = (sub % N_SUB_IN) * SUB_IN, co0 = (sub / N_SUB_IN) * SUB_OUT;
@@ -582,9 +575,8 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     }
     float *part = static_cast<float *>(workspace);
     if (n_chunks > 0) {
-        // 16-byte row reads: rows are 512 bytes, so it is the two base addresses that decide
-        const bool rows_aligned = ((reinterpret_cast<uintptr_t>(a.feat) | reinterpret_cast<uintptr_t>(a.dense)) & 15) == 0;
-        if (BF16 && C_IN == 256 && C_OUT == 256 && rows_aligned) {
+        // (16-byte row reads: the entry point has checked that x and dy are 16-byte aligned, and rows are 512 bytes)
+        if constexpr (BF16 && C_IN == 256 && C_OUT == 256) {
             PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&weight_lds_kernel),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * LDS_BATCH_BYTES));
             weight_lds_kernel<<<(unsigned)n_chunks, LDS_WAVES * 64, 2 * LDS_BATCH_BYTES, stream>>>(
@@ -595,7 +587,7 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
                 static_cast<const float *>(a.feat), static_cast<const float *>(a.dense), part, tri_o, a.gather, seg, a.K,
                 a.n_triplets, chunk, n_chunks);
         else if constexpr (BF16)
-            weight_wide_kernel<C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)(N_SUB == 2 * WAVES ? ceil_div(n_chunks, (int64_t)8) * 16 : ceil_div(n_chunks * N_SUB, WAVES)), WAVES * 64, 0, stream>>>(
+            weight_wide_kernel<C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
                 a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
         else
             weight_kernel<BF16, C_IN, C_OUT, SUB_IN, SUB_OUT><<<(unsigned)ceil_div(n_chunks * N_SUB, WAVES), WAVES * 64, 0, stream>>>(
