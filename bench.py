@@ -202,6 +202,24 @@ def main() -> int:
     gb = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
     gemm_tflops = 2 * 8192 ** 3 / timed(lambda: torch.matmul(ga, gb), 5) / 1e12
     del ga, gb
+    # and on a loop that only issues bf16 MFMAs on registers (eight waves per SIMD, sixteen independent chains each)
+    # (a measurement aid in a shared object of its own; reported as null if it has not been built)
+    import ctypes
+    mfma_loop_tflops = None
+    probe_path = os.path.join(ROOT, "paper_2511_23227_amd", "libpcpp_probe.so")
+    if os.path.exists(probe_path):
+        probe = ctypes.CDLL(probe_path)
+        probe.pcpp_probe_mfma_bf16.restype = ctypes.c_double
+        probe.pcpp_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+        probe_flops = []
+
+        def run_probe():
+            f = probe.pcpp_probe_mfma_bf16(256 * 8, 4096, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            assert f > 0, "peak probe failed to launch"
+            probe_flops.append(f)
+        secs = timed(run_probe, 5)
+        mfma_loop_tflops = probe_flops[-1] / secs / 1e12
 
     def roofline(op):
         b = algorithmic_bytes(op, n_t, s.n_in, s.n_out, s.c_in, s.c_out, s.K, s_in, 4)
@@ -250,6 +268,8 @@ def main() -> int:
             per_op[op]["mfma_frac"] = round(tf / peak, 4)
             if peak == MFMA_PEAK_TFLOPS["bf16"]:
                 per_op[op]["mfma_frac_of_measured_gemm"] = round(tf / gemm_tflops, 4)
+                if mfma_loop_tflops:
+                    per_op[op]["mfma_frac_of_issue_loop"] = round(tf / mfma_loop_tflops, 4)
             if s.dtype == "bf16" and min(s.c_in, s.c_out) >= 256:   # wide layers are matrix-core bound
                 per_op[op].update({"bound": "mfma", "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s",
                                    "frac": round(tf / peak, 4)})
@@ -269,7 +289,8 @@ def main() -> int:
         "op_ms_median": {k_: round(float(np.median(v)), 4) for k_, v in samples.items()},
         "op_ms_min": {k_: round(float(v.min()), 4) for k_, v in samples.items()},
         "op_ms_cold": {k_: round(v, 4) for k_, v in cold_ms.items()},
-        "measured_peaks": {"copy_GBs": round(copy_gbs, 1), "gemm_bf16_TFLOPs": round(gemm_tflops, 1)},
+        "measured_peaks": {"copy_GBs": round(copy_gbs, 1), "gemm_bf16_TFLOPs": round(gemm_tflops, 1),
+                           "mfma_issue_loop_bf16_TFLOPs": None if mfma_loop_tflops is None else round(mfma_loop_tflops, 1)},
         "triplets_per_k_o_pair": pair_ratio,
         "pairs_per_s": {k_: round(n_t / (v * 1e-3), 1) for k_, v in op_ms.items()},
         "roofline": per_op[dominant],

@@ -11,6 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpcpp.so")
+PROBE_LIB = os.path.join(HERE, "libpcpp_probe.so")     # the benchmark's peak-rate probe, outside the library's interface
 
 # file -> extra flags.  The search kernels must not contract a*b+c into an FMA: the inclusion test
 # is a fixed binary64 operation sequence shared with the CPU oracle by convention.
@@ -51,6 +52,10 @@ def build(verbose: bool = False) -> str:
     tmp = LIB + ".tmp"
     subprocess.run(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs, check=True)
     os.replace(tmp, LIB)
+    probe = _compile("peak_probe.hip", [])
+    tmp = PROBE_LIB + ".tmp"
+    subprocess.run(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, probe], check=True)
+    os.replace(tmp, PROBE_LIB)
     if verbose:
         print("built", LIB)
     return LIB
