@@ -550,14 +550,34 @@ __global__ __launch_bounds__(256) void weight_reduce(const float *__restrict__ p
     }
 }
 
-// triplets per chunk: at least 512, grown so that there are at most about 8192 chunks (2048 for wide
-// layers, whose partial sums are large)
-int weight_chunk(int64_t n_triplets, int c_in, int c_out)
+// Triplets per chunk.  The blocks of a launch (`per_block` chunks each) are spread evenly over the CUs, and the
+// kernels run at a fixed rate per CU, so a launch takes as long as the CU with the most blocks: the chunk length
+// is chosen so that the number of blocks is a whole multiple m of the CU count, with about a thousand triplets
+// per chunk and at most 8192 chunks (2048 for wide layers, whose partial sums are large).  Clouds too small for
+// one block per CU keep chunks of 512.
+constexpr int64_t DEVICE_CUS = 256;           // MI355X
+
+int weight_chunk(int64_t n_triplets, int c_in, int c_out, int per_block)
 {
     const int64_t max_chunks = (int64_t)c_in * c_out >= 128 * 128 ? 2048 : 8192;
-    int chunk = 512;
-    while ((n_triplets + chunk - 1) / chunk > max_chunks) chunk *= 2;
-    return chunk;
+    const int64_t per_round = DEVICE_CUS * per_block;                  // chunks of one block on every CU
+    int64_t m = (n_triplets + per_round * 500) / (per_round * 1000);     // nearest whole number of rounds
+    if (m > max_chunks / per_round) m = max_chunks / per_round;
+    if (m < 1 || n_triplets < per_round * 512) {
+        int chunk = 512;
+        while ((n_triplets + chunk - 1) / chunk > max_chunks) chunk *= 2;
+        return chunk;
+    }
+    const int64_t chunk = ceil_div(n_triplets, per_round * m);
+    return (int)((chunk + 31) / 32 * 32);
+}
+
+// chunks handled by one block of the kernel that serves the shape
+int weight_chunks_per_block(bool bf16, int c_in, int c_out)
+{
+    if (bf16 && c_in == 256 && c_out == 256) return 1;                 // weight_lds_kernel
+    if (bf16 && c_in >= 128 && c_out >= 128) return WAVES / 2;          // two sub-block waves per chunk
+    return WAVES;                                                       // one wave per chunk
 }
 
 template <bool BF16, int C_IN, int C_OUT, int SUB_IN = C_IN, int SUB_OUT = C_OUT>
@@ -565,7 +585,7 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
                   size_t workspace_bytes, hipStream_t stream)
 {
     const int n_elem = C_IN * C_OUT;
-    const int chunk = weight_chunk(a.n_triplets, C_IN, C_OUT);
+    const int chunk = weight_chunk(a.n_triplets, C_IN, C_OUT, weight_chunks_per_block(BF16, C_IN, C_OUT));
     const int64_t n_chunks = ceil_div(a.n_triplets, chunk);
     constexpr int N_SUB = (C_IN / SUB_IN) * (C_OUT / SUB_OUT);
     const size_t need = (size_t)(n_chunks + a.K) * n_elem * sizeof(float);
@@ -630,7 +650,7 @@ int mvmr_weight_mfma(const MvmrArgs &a, float *dw, const int32_t *tri_o, const i
 size_t mvmr_weight_mfma_workspace_bytes(int64_t n_triplets, int c_in, int c_out, int K, int in_dtype)
 {
     if (!weight_shape_supported(in_dtype, c_in, c_out)) return 0;
-    const int chunk = weight_chunk(n_triplets, c_in, c_out);
+    const int chunk = weight_chunk(n_triplets, c_in, c_out, weight_chunks_per_block(in_dtype == PCPP_BF16, c_in, c_out));
     return align_up((size_t)(ceil_div(n_triplets, chunk) + K) * c_in * c_out * sizeof(float));
 }
 
