@@ -523,29 +523,38 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
 }
 
 // dw[k][e] = (partial of the run's head, if it starts inside a chunk) + partials of the chunks whose first
-// triplet lies in run k.  16 threads share one element: thread g adds chunks c0+g, c0+g+16, ... in
-// ascending order and the 16 sums are then added in order of g, so the result is reproducible.
-// grid = (ceil(c_out*c_in / 16), K), block = 256
-__global__ __launch_bounds__(256) void weight_reduce(const float *__restrict__ part, float *__restrict__ dw,
-                                                     const int64_t *__restrict__ seg, int n_elem, int chunk,
-                                                     int64_t n_chunks)
+// triplet lies in run k.  A block of four waves owns 64 consecutive elements of one cell: wave w adds chunks
+// c0 + w, c0 + w + 4, ... in ascending order (each read is 256 contiguous bytes) and the four sums are then
+// added in order of w, so the result is reproducible.  grid = (ceil(c_out*c_in / 64), K), block = 256
+constexpr int REDUCE_WAVES = 4;
+
+__global__ __launch_bounds__(REDUCE_WAVES * 64) void weight_reduce(const float *__restrict__ part, float *__restrict__ dw,
+                                                                   const int64_t *__restrict__ seg, int n_elem, int chunk,
+                                                                   int64_t n_chunks)
 {
-    __shared__ float sums[16][17];
-    const int el = threadIdx.x & 15, g = threadIdx.x >> 4;
-    const int e = blockIdx.x * 16 + el;
+    __shared__ float sums[REDUCE_WAVES][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + lane;
     const int k = blockIdx.y;
     const int64_t s = seg[k], t = seg[k + 1];
     float v = 0.f;
     if (t > s && e < n_elem) {
         const int64_t c0 = (s + chunk - 1) / chunk, c1 = (t + chunk - 1) / chunk;
-        for (int64_t c = c0 + g; c < c1; c += 16) v += part[(size_t)c * n_elem + e];
+        const float *src = part + (size_t)e;
+        int64_t c = c0 + wave;
+        for (; c + 3 * REDUCE_WAVES < c1; c += 4 * REDUCE_WAVES) {      // four independent reads in flight
+            const float v0 = src[(size_t)c * n_elem], v1 = src[(size_t)(c + REDUCE_WAVES) * n_elem];
+            const float v2 = src[(size_t)(c + 2 * REDUCE_WAVES) * n_elem], v3 = src[(size_t)(c + 3 * REDUCE_WAVES) * n_elem];
+            v = (((v + v0) + v1) + v2) + v3;
+        }
+        for (; c < c1; c += REDUCE_WAVES) v += src[(size_t)c * n_elem];
     }
-    sums[g][el] = v;
+    sums[wave][lane] = v;
     __syncthreads();
-    if (g == 0 && e < n_elem) {
+    if (wave == 0 && e < n_elem) {
         float r = (t > s && s % chunk != 0) ? part[(size_t)(n_chunks + k) * n_elem + e] : 0.f;
 #pragma unroll
-        for (int gg = 0; gg < 16; ++gg) r += sums[gg][el];
+        for (int w = 0; w < REDUCE_WAVES; ++w) r += sums[w][lane];
         dw[(size_t)k * n_elem + e] = r;
     }
 }
@@ -614,8 +623,8 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
                 a.feat, a.dense, part, tri_o, a.gather, seg, a.K, a.n_triplets, chunk, n_chunks);
         PCPP_HIP_CHECK(hipGetLastError());
     }
-    dim3 grid((unsigned)ceil_div(n_elem, 16), (unsigned)a.K);
-    weight_reduce<<<grid, 256, 0, stream>>>(part, dw, seg, n_elem, chunk, n_chunks);
+    dim3 grid((unsigned)ceil_div(n_elem, 64), (unsigned)a.K);
+    weight_reduce<<<grid, REDUCE_WAVES * 64, 0, stream>>>(part, dw, seg, n_elem, chunk, n_chunks);
     PCPP_HIP_CHECK(hipGetLastError());
     return PCPP_OK;
 }
