@@ -1,4 +1,6 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import zlib
+
 import numpy as np
 import pytest
 import torch
@@ -87,10 +89,12 @@ def test_scene_full(pcpp, sid):
     # wide layers (W shared through LDS), K = 125 and K = 27, ragged point counts
     dict(n_in=1500, n_out=1300, r=0.15, t=5, cin=256, cout=256, dt="bf16"),
     dict(n_in=700, n_out=900, r=0.2, t=3, cin=128, cout=128, dt="bf16"),
+    # enough triplets for the weight gradient to balance its chunks over the CUs (two sub-block waves per chunk)
+    dict(n_in=5000, n_out=5000, r=0.15, t=3, cin=128, cout=128, dt="bf16"),
 ])
 def test_small_shapes(pcpp, case):
     """Ragged sizes: n_out != n_in, partial tiles, channel counts that are not multiples of anything."""
-    rng = np.random.default_rng(hash(tuple(sorted(case.items()))) & 0xffff)
+    rng = np.random.default_rng(zlib.crc32(repr(sorted(case.items())).encode()))
     pin = rng.uniform(0, 1, (case["n_in"], 3)).astype(np.float32)
     pout = rng.uniform(0, 1, (case["n_out"], 3)).astype(np.float32)
     K = case["t"] ** 3
