@@ -28,10 +28,10 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 MEASURED_TRAFFIC: dict = {
     (2, "default", "fwd"): int(289.4e6 + 16.0e6),         # rows_kernel: scaled FETCH_SIZE + WRITE_SIZE
     (2, "default", "bwd_input"): int(289.4e6 + 16.0e6),
-    (2, "default", "bwd_weight"): int(390.6e6 + 19.8e6),  # weight_f32_kernel (weight_reduce adds 39.7e6 read)
-    (5, "default", "fwd"): int(27531e6 + 1024e6),         # rows_wide_kernel
-    (5, "default", "bwd_input"): int(27531e6 + 1024e6),
-    (5, "default", "bwd_weight"): int(25409e6 + 543e6),   # weight_lds_kernel (weight_reduce adds 1086e6 read)
+    (2, "default", "bwd_weight"): int(388.4e6 + 8.4e6),   # weight_f32_kernel (weight_reduce adds 8.5e6 read)
+    (5, "default", "fwd"): int(27668e6 + 1024e6),         # rows_wide_kernel
+    (5, "default", "bwd_input"): int(27668e6 + 1024e6),
+    (5, "default", "bwd_weight"): int(25407e6 + 567e6),   # weight_lds_kernel (weight_reduce adds 567e6 read)
 }
 
 
