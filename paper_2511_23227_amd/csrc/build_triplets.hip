@@ -212,6 +212,7 @@ struct Candidates {
 };
 
 constexpr uint32_t SMALL_LIST = 160;      // up to this many neighbours the all-pairs rank is cheaper than bucketing
+constexpr uint32_t BUCKET_FROM = 64;      // ... and from here on bucketing through LDS adds is cheaper, when keys pack
 constexpr int HIT_INDEX_BITS = 24;         // a stored hit = cell << 24 | candidate index
 constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
 
@@ -314,9 +315,10 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                                                              int32_t *__restrict__ out_k,
                                                              uint32_t *__restrict__ run_start_out, int list_cap,
                                                              const uint32_t *__restrict__ hits, uint32_t hit_stride,
-                                                             uint32_t out_cap, int64_t *__restrict__ seg_out)
+                                                             uint32_t out_cap, int64_t *__restrict__ seg_out,
+                                                             int pack_ok)
 {
-    extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run
+    extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run, then [SEARCH_WAVES][K] bucket words
     __shared__ uint32_t list_all[SEARCH_WAVES][LIST_CAP_MAX];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
@@ -399,6 +401,69 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
         const int64_t a = tile * TILE + al;
         if (a >= n_centres) break;             // wave-uniform
         if (n_of[u] == 0) continue;            // wave-uniform
+        if (pack_ok && n_of[u] > BUCKET_FROM && n_of[u] <= (uint32_t)list_cap) {
+            // Longer lists, when cell and candidate index fit one word (cell << 24 | index).  The keys -- read back from the count pass
+            // when it kept them, found again otherwise -- are dropped into per-cell buckets of the list through one
+            // LDS word per cell (bucket start << 16 | fill count, advanced with an LDS add; the order inside a
+            // bucket is whatever the adds made it), and each key's rank among the smaller keys of its own bucket
+            // is its final slot: a key is compared with its cell's neighbours only.
+            const uint32_t n = n_of[u];
+            uint32_t *wk = tbl + K * TILE + wave * K;
+            uint32_t run = 0;
+            for (int k0 = 0; k0 < K; k0 += 64) {
+                const int k = k0 + lane;
+                const uint32_t c1 = k < K ? cnt_tile[k * TILE + al] : 0u;
+                const uint32_t inc = wave_incl_scan_u32(c1, lane);
+                if (k < K) wk[k] = (run + inc - c1) << 16;
+                run += (uint32_t)__shfl((int)inc, 63, 64);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (n <= reuse_max) {
+                const uint32_t *mine = hits + (size_t)a * hit_stride;
+                for (uint32_t e = lane; e < n; e += 64) {
+                    const uint32_t key = mine[e];
+                    const uint32_t old = atomicAdd(&wk[key >> HIT_INDEX_BITS], 1u);
+                    list[(old >> 16) + (old & 0xffffu)] = key;
+                }
+            } else {
+                Candidates<SWAP> &c = cand[0];
+                c.open(centres, a, g, lane);
+                for (uint32_t base = 0; base < c.total; base += 64) {
+                    int b, k;
+                    if (c.fetch(base + lane, g, q, b, k)) {
+                        const uint32_t old = atomicAdd(&wk[k], 1u);
+                        list[(old >> 16) + (old & 0xffffu)] = ((uint32_t)k << HIT_INDEX_BITS) | (uint32_t)b;
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (uint32_t e0 = 0; e0 < n; e0 += 64) {
+                const uint32_t e = e0 + lane;
+                const bool have = e < n;
+                const uint32_t key = have ? list[e] : 0u;
+                const int k = (int)(key >> HIT_INDEX_BITS);
+                const uint32_t w = have ? wk[k] : 0u;
+                const uint32_t b0 = w >> 16, nk = w & 0xffffu;
+                uint32_t rank = 0;
+                for (uint32_t j = 0; __ballot(j < nk) != 0ull; ++j) {
+                    const uint32_t v = j < nk ? list[b0 + j] : 0xffffffffu;
+                    rank += v < key ? 1u : 0u;
+                }
+                if (have) {
+                    const uint32_t pos = tbl[k * TILE + al] + rank;
+                    if (pos < out_cap) {
+                        if (out_c) out_c[pos] = (int32_t)a;
+                        if (out_b) out_b[pos] = (int32_t)(key & HIT_INDEX_MASK);
+                        if (out_k) out_k[pos] = k;
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            continue;
+        }
         if (n_of[u] <= reuse_max && n_of[u] <= (uint32_t)list_cap) {
             // rank the stored (cell, index) keys by comparing all pairs
             const uint32_t n = n_of[u];
@@ -818,16 +883,21 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
 
     const int64_t nt_o = ceil_div(n_out, TILE);
     const size_t lds = (size_t)K * TILE * sizeof(uint32_t);
+    // the second pass also keeps one bucket word per (wave, cell); a key packs cell and candidate index into 32 bits
+    const size_t lds_fill = lds + (size_t)SEARCH_WAVES * K * sizeof(uint32_t);
+    const int pack_ok = K <= 256 && n_in < (1 << HIT_INDEX_BITS) && n_out < (1 << HIT_INDEX_BITS);
     if (lds > (size_t)32 * 1024) {
         // large t: the per-tile table plus the neighbour lists exceed the default dynamic LDS limit
         PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<true, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    if (lds_fill > (size_t)32 * 1024) {
         PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fill));
         PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fill));
     }
     const bool want_fwd_plan = plan && (plan_flags & PCPP_PLAN_FWD) && !count_only;
     const bool want_bwd_plan = plan && (plan_flags & PCPP_PLAN_BWD_INPUT) && !count_only;
@@ -896,10 +966,10 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     const uint32_t tri_cap = (uint32_t)(capacity < (int64_t)INT32_MAX ? capacity : (int64_t)INT32_MAX);
     if (nt_o > 0) {
         uint32_t *f_runs = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
-        query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
+        query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
                                                                         f_off, tri_o, tri_i, tri_k, f_runs,
                                                                         g_list_cap, f_hits, bs.fwd_stride, tri_cap,
-                                                                        seg_offsets);
+                                                                        seg_offsets, pack_ok);
         PCPP_HIP_CHECK(hipGetLastError());
     } else {
         // no outputs: every run starts at 0
@@ -930,10 +1000,10 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch(3), nullptr, stream)) != PCPP_OK)
             return rc;
         if (nt_i > 0) {
-            query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
+            query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
                                                                            b_ptr, nullptr, b_gather, nullptr, b_runs,
                                                                            g_list_cap, b_hits, bs.bwd_stride, gather_cap,
-                                                                           nullptr);
+                                                                           nullptr, pack_ok);
             PCPP_HIP_CHECK(hipGetLastError());
         }
     }
