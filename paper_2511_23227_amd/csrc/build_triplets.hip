@@ -212,6 +212,7 @@ struct Candidates {
 };
 
 constexpr uint32_t SMALL_LIST = 160;      // up to this many neighbours the all-pairs rank is cheaper than bucketing
+constexpr uint32_t KEEP_MAX = 256;        // longest neighbour list the count pass keeps per centre
 constexpr uint32_t BUCKET_FROM = 64;      // ... and from here on bucketing through LDS adds is cheaper, when keys pack
 constexpr int HIT_INDEX_BITS = 24;         // a stored hit = cell << 24 | candidate index
 constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
@@ -234,11 +235,11 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
                                                               CountOut side, CountOut mirror, uint32_t hit_stride)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE], with BOTH followed by the mirror side's [K][TILE]
-    __shared__ uint32_t stage[(BOTH ? 2 : 1) * SEARCH_WAVES * SMALL_LIST];   // hit lists on their way to memory
+    __shared__ uint32_t stage[(BOTH ? 2 : 1) * SEARCH_WAVES * KEEP_MAX];   // hit lists on their way to memory
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
     uint32_t *tbl2 = tbl + K * TILE;
-    uint32_t *mine = stage + wave * SMALL_LIST, *mine2 = stage + (SEARCH_WAVES + wave) * SMALL_LIST;
+    uint32_t *mine = stage + wave * KEEP_MAX, *mine2 = stage + (SEARCH_WAVES + wave) * KEEP_MAX;
     for (int idx = threadIdx.x; idx < (BOTH ? 2 : 1) * K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
     __syncthreads();
     const bool keep = side.hits != nullptr;
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
     const unsigned long long lane_lt = (1ull << lane) - 1ull;
     // A centre whose neighbours the count pass left in `hits` needs no second search.
     constexpr int PER_WAVE = TILE / SEARCH_WAVES;
-    const uint32_t reuse_max = hits ? (hit_stride < SMALL_LIST ? hit_stride : SMALL_LIST) : 0u;
+    const uint32_t reuse_max = hits ? (hit_stride < KEEP_MAX ? hit_stride : KEEP_MAX) : 0u;
     Candidates<SWAP> cand[1];
     uint32_t n_of[PER_WAVE];
 #pragma unroll
@@ -666,13 +667,13 @@ struct BuildScratch {
     size_t fwd_hits_off = 0, bwd_hits_off = 0, end_with_hits = 0;
 };
 
-// list length per centre: twice the mean neighbour count, within [32, SMALL_LIST]
+// list length per centre: twice the mean neighbour count, within [32, KEEP_MAX]
 uint32_t hit_stride_for(int64_t capacity, int64_t n_centres)
 {
     if (n_centres <= 0 || capacity <= 0) return 0;
     int64_t s = (2 * ceil_div(capacity, n_centres) + 15) / 16 * 16;
     if (s < 32) s = 32;
-    if (s > (int64_t)SMALL_LIST) s = SMALL_LIST;
+    if (s > (int64_t)KEEP_MAX) s = KEEP_MAX;
     return (uint32_t)s;
 }
 
@@ -913,7 +914,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         int dev = 0, per_block = 0;
         PCPP_HIP_CHECK(hipGetDevice(&dev));
         PCPP_HIP_CHECK(hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
-        if (2 * lds + (size_t)8 * 1024 > (size_t)per_block) one_pass = false;
+        if (2 * lds + (size_t)2 * SEARCH_WAVES * KEEP_MAX * sizeof(uint32_t) + 1024 > (size_t)per_block) one_pass = false;
         else
             PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false, true>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * lds)));
