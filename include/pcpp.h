@@ -2,8 +2,11 @@
  * pcpp -- convolution on native points (PointCNN++) as MVMR, MI355X (gfx950) only.
  *
  * C ABI of libpcpp.so.  Plain pointers and sizes; every pointer is a DEVICE pointer unless the
- * comment says HOST.  The caller owns every buffer (inputs, outputs, plan, workspace); the library
- * allocates nothing on these paths and keeps no state between calls.
+ * comment says HOST.  The caller owns every buffer (inputs, outputs, plan, workspace).  The calls
+ * below allocate no device or host memory and keep no data between calls; the only thing the
+ * library remembers is, per kernel and device, that it has raised that kernel's dynamic LDS limit
+ * (an idempotent attribute of the loaded code).  pcpp_build_triplets creates one event and destroys
+ * it before it returns.
  *
  * Notation (paper -> here): output index i -> o, input index j -> i, kernel cell k;
  * t = kernel resolution per axis, K = t^3; T = the triplet set {(o, i, k)}.
@@ -16,6 +19,10 @@
  *   - outputs are overwritten, never accumulated into; rows without a triplet are zero.
  *   - indices are int32 (n_in, n_out, |T| < 2^31), segment offsets int64, coordinates fp32.
  *   - feature tensors are row-major, 16-byte aligned; dtype codes below.
+ *   - feature tensors (x, dy, w) must hold finite values.  The matrix-core kernels form the sum of the
+ *     source rows of a (cell, output) run as a product with a 0/1 selection matrix or stage it beside other
+ *     rows, so an Inf or NaN in one source row can reach destination rows that have no triplet with it
+ *     (within the same group of up to 128 consecutive centres).  Coordinates must be finite too.
  */
 #ifndef PCPP_H_
 #define PCPP_H_
@@ -27,26 +34,45 @@
 extern "C" {
 #endif
 
+#if defined(__GNUC__)
+#define PCPP_API __attribute__((visibility("default")))
+#else
+#define PCPP_API
+#endif
+
 #define PCPP_OK                 0
 #define PCPP_ERR_INVALID_ARG   -1  /* null pointer, negative size, t < 1, bad radius, misaligned    */
 #define PCPP_ERR_CAPACITY      -2  /* triplet buffers too small; *n_triplets holds the needed count */
 #define PCPP_ERR_WORKSPACE     -3  /* workspace or plan buffer smaller than the matching *_bytes()  */
 #define PCPP_ERR_UNSUPPORTED   -4  /* dtype / shape outside what the library handles                */
-#define PCPP_ERR_HIP           -5  /* a HIP runtime call failed                                     */
+#define PCPP_ERR_HIP           -5  /* a HIP runtime call failed, or a device-side wait ran out      */
 
 #define PCPP_F32   0   /* IEEE binary32                    */
 #define PCPP_BF16  1   /* bfloat16, round-to-nearest-even  */
 
+/* plan_flags: which parts of a plan pcpp_build_triplets writes, and how.  The same value must be passed
+ * to every compute call that reads the plan. */
 #define PCPP_PLAN_FWD        1   /* what pcpp_mvmr_fwd and pcpp_mvmr_bwd_weight read */
 #define PCPP_PLAN_BWD_INPUT  2   /* what pcpp_mvmr_bwd_input reads (only together with PCPP_PLAN_FWD) */
+#define PCPP_PLAN_SPATIAL    4   /* the plan groups the centres along a space-filling curve computed by the
+                                    library instead of in index order: the centres a kernel block owns are then
+                                    neighbours in space whatever the caller's point order, which wide layers need
+                                    (they share source rows and weight slices through the caches).  The public
+                                    triplet arrays, every result and every tolerance are unchanged; the build
+                                    takes about a third longer. */
+/* testing aids, accepted in plan_flags by pcpp_build_triplets only; results are identical with or without */
+#define PCPP_BUILD_TEST_SHORT_LISTS  0x100  /* keep at most 40 neighbours of a centre on chip: longer lists take
+                                               the path that ranks by scanning the candidates again          */
+#define PCPP_BUILD_TEST_WIDE_KEYS    0x200  /* treat cell and index as too wide to share one 32-bit word, as for
+                                               clouds of 2^24 points or more                                  */
 
 #define PCPP_MAX_T  6            /* K = t^3 <= 216 */
 
 /* Message for the last error returned on the calling thread (never NULL). HOST. */
-const char *pcpp_last_error(void);
+PCPP_API const char *pcpp_last_error(void);
 
 /* Library version, major*100 + minor. */
-int pcpp_version(void);
+PCPP_API int pcpp_version(void);
 
 /* ---------------------------------------------------------------------------------------------
  * Triplet construction: Sec. 3.2 "Definition" with the fixed radius search of Sec. 4.1, followed
@@ -61,9 +87,13 @@ int pcpp_version(void);
  *   tri_o, tri_i, tri_k  [capacity] int32: T in ascending (k, o, i) order.  All three NULL =>
  *                        count only (capacity, seg_offsets and plan are ignored).
  *   seg_offsets          [K+1] int64: start of each cell's run; seg_offsets[K] = |T|.
- *   n_triplets           HOST int64: |T|, also set when PCPP_ERR_CAPACITY is returned.
+ *   n_triplets           HOST int64: |T|, also set when PCPP_ERR_CAPACITY is returned.  If it points into
+ *                        pinned host memory (hipHostMalloc) the device writes the count straight into it
+ *                        and the second pass is queued without waiting for the host; with pageable memory
+ *                        the call copies the count synchronously first (same results, the GPU idles for one
+ *                        round trip).
  *   plan                 optional opaque buffer of pcpp_plan_bytes(...) bytes that the three
- *                        compute calls need: per-(cell, output) neighbour counts and tile offsets
+ *                        compute calls need: per-(cell, centre) neighbour runs and tile offsets
  *                        for the forward / weight-gradient pass (PCPP_PLAN_FWD) and the same
  *                        triplets regrouped by (k, i, o) for the input gradient
  *                        (PCPP_PLAN_BWD_INPUT).  plan_flags selects the parts; NULL => none.
@@ -74,40 +104,43 @@ int pcpp_version(void);
  *                        (same results, about a third less time).
  * in_xyz [n_in,3] and out_xyz [n_out,3] may alias (outputs at the inputs).
  * Errors: INVALID_ARG (null xyz with n > 0, radius not finite or <= 0, t outside 1..PCPP_MAX_T,
- * some but not all tri_* NULL), CAPACITY, WORKSPACE, UNSUPPORTED (|T| >= 2^31), HIP.
+ * some but not all tri_* NULL, unknown flag bits), CAPACITY, WORKSPACE, UNSUPPORTED (|T| >= 2^31), HIP.
  * Non-finite coordinates are not supported (undefined triplets, no fault).
  * ------------------------------------------------------------------------------------------- */
-size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t);
-size_t pcpp_build_triplets_workspace_bytes_for(int64_t n_in, int64_t n_out, int t, int64_t capacity);
-size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags);
+PCPP_API size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t);
+PCPP_API size_t pcpp_build_triplets_workspace_bytes_for(int64_t n_in, int64_t n_out, int t, int64_t capacity);
+PCPP_API size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags);
 
-int pcpp_build_triplets(const float *in_xyz, int64_t n_in,
-                        const float *out_xyz, int64_t n_out,
-                        float radius, int t,
-                        int32_t *tri_o, int32_t *tri_i, int32_t *tri_k, int64_t capacity,
-                        int64_t *seg_offsets,
-                        int64_t *n_triplets,
-                        void *plan, size_t plan_bytes, int plan_flags,
-                        void *workspace, size_t workspace_bytes,
-                        void *stream);
+PCPP_API int pcpp_build_triplets(const float *in_xyz, int64_t n_in,
+                                 const float *out_xyz, int64_t n_out,
+                                 float radius, int t,
+                                 int32_t *tri_o, int32_t *tri_i, int32_t *tri_k, int64_t capacity,
+                                 int64_t *seg_offsets,
+                                 int64_t *n_triplets,
+                                 void *plan, size_t plan_bytes, int plan_flags,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * MVMR forward, Eq. (1) of Sec. 3.1.1:  out[o, :] = sum_{(o,i,k) in T} W[k] x[i, :].
  *   x   [n_in , c_in ]  in_dtype        w  [K, c_out, c_in] in_dtype (the paper's layout, Sec. 3.3.2)
  *   out [n_out, c_out]  out_dtype (PCPP_F32, or PCPP_BF16 when in_dtype is PCPP_BF16)
  * Products are accumulated in fp32.  tri_* / seg_offsets / plan must be exactly what one
- * pcpp_build_triplets call produced for these n_in, n_out, K (with PCPP_PLAN_FWD); anything else
- * is undefined behaviour.  workspace: pcpp_mvmr_workspace_bytes(...) bytes, 256-byte aligned.
- * Errors: INVALID_ARG, WORKSPACE, UNSUPPORTED (c_in or c_out < 1 or > 1024, dtype combination).
+ * pcpp_build_triplets call produced for these n_in, n_out, K with these plan_flags (which must include
+ * PCPP_PLAN_FWD); anything else is undefined behaviour.  plan_bytes is the size of the plan buffer.
+ * workspace: pcpp_mvmr_workspace_bytes(...) bytes, 256-byte aligned.
+ * Errors: INVALID_ARG (also: plan_flags lack the part this call reads), WORKSPACE (also: plan_bytes smaller
+ * than pcpp_plan_bytes for these sizes and flags), UNSUPPORTED (c_in or c_out < 1 or > 1024, dtype combination).
  * ------------------------------------------------------------------------------------------- */
-size_t pcpp_mvmr_workspace_bytes(int op /*0 fwd, 1 bwd_input, 2 bwd_weight*/, int64_t n_in, int64_t n_out,
-                                 int64_t n_triplets, int c_in, int c_out, int K, int in_dtype);
+PCPP_API size_t pcpp_mvmr_workspace_bytes(int op /*0 fwd, 1 bwd_input, 2 bwd_weight*/, int64_t n_in, int64_t n_out,
+                                          int64_t n_triplets, int c_in, int c_out, int K, int in_dtype);
 
-int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out_dtype,
-                  int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
-                  const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
-                  const int64_t *seg_offsets, int64_t n_triplets,
-                  const void *plan, void *workspace, size_t workspace_bytes, void *stream);
+PCPP_API int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out_dtype,
+                           int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                           const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                           const int64_t *seg_offsets, int64_t n_triplets,
+                           const void *plan, size_t plan_bytes, int plan_flags,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * MVMR backward w.r.t. the input features, first gradient equation of Sec. 3.3.3:
@@ -115,22 +148,24 @@ int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out
  *   dy [n_out, c_out] in_dtype,  w [K, c_out, c_in] in_dtype,  dx [n_in, c_in] out_dtype.
  * Needs a plan built with PCPP_PLAN_BWD_INPUT.  Otherwise as pcpp_mvmr_fwd.
  * ------------------------------------------------------------------------------------------- */
-int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, int out_dtype,
-                        int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
-                        const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
-                        const int64_t *seg_offsets, int64_t n_triplets,
-                        const void *plan, void *workspace, size_t workspace_bytes, void *stream);
+PCPP_API int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, int out_dtype,
+                                 int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                                 const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                                 const int64_t *seg_offsets, int64_t n_triplets,
+                                 const void *plan, size_t plan_bytes, int plan_flags,
+                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Backward w.r.t. the weights (VVOR), Eq. (5) of Sec. 3.3.3:
  *   dw[k] = sum_{(o,i,k) in T} dy[o, :] (outer) x[i, :],   dw [K, c_out, c_in] always fp32.
  * Cells with no triplet get exact zeros.  Needs a plan built with PCPP_PLAN_FWD.
  * ------------------------------------------------------------------------------------------- */
-int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype,
-                         int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
-                         const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
-                         const int64_t *seg_offsets, int64_t n_triplets,
-                         const void *plan, void *workspace, size_t workspace_bytes, void *stream);
+PCPP_API int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype,
+                                  int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                                  const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                                  const int64_t *seg_offsets, int64_t n_triplets,
+                                  const void *plan, size_t plan_bytes, int plan_flags,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

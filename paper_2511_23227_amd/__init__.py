@@ -4,8 +4,11 @@ The package is a thin ctypes binding over libpcpp.so (see include/pcpp.h).  Ever
 path -- hashed-grid radius search, reordering by (k, o), MVMR forward and both gradients -- runs
 in the library's kernels; PyTorch only provides device memory and the stream.
 """
-from .binding import (PLAN_BWD_INPUT, PLAN_FWD, PcppError, Triplets, library, pcpp_build_triplets,
-                      pcpp_mvmr_bwd_input, pcpp_mvmr_bwd_weight, pcpp_mvmr_fwd)
+from . import binding
+from .binding import (BUILD_TEST_SHORT_LISTS, BUILD_TEST_WIDE_KEYS, PLAN_BWD_INPUT, PLAN_FWD, PLAN_SPATIAL, PcppError,
+                      Triplets, library, pcpp_build_triplets, pcpp_count_triplets, pcpp_mvmr_bwd_input,
+                      pcpp_mvmr_bwd_weight, pcpp_mvmr_fwd)
 
-__all__ = ["PLAN_BWD_INPUT", "PLAN_FWD", "PcppError", "Triplets", "library", "pcpp_build_triplets",
-           "pcpp_mvmr_bwd_input", "pcpp_mvmr_bwd_weight", "pcpp_mvmr_fwd"]
+__all__ = ["BUILD_TEST_SHORT_LISTS", "BUILD_TEST_WIDE_KEYS", "PLAN_BWD_INPUT", "PLAN_FWD", "PLAN_SPATIAL", "PcppError",
+           "Triplets", "binding", "library", "pcpp_build_triplets", "pcpp_count_triplets", "pcpp_mvmr_bwd_input",
+           "pcpp_mvmr_bwd_weight", "pcpp_mvmr_fwd"]

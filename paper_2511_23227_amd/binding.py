@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import threading
 from dataclasses import dataclass
 
 import torch
@@ -11,7 +12,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpcpp.so")
 
 PCPP_F32, PCPP_BF16 = 0, 1
-PLAN_FWD, PLAN_BWD_INPUT = 1, 2
+PLAN_FWD, PLAN_BWD_INPUT, PLAN_SPATIAL = 1, 2, 4
+BUILD_TEST_SHORT_LISTS, BUILD_TEST_WIDE_KEYS = 0x100, 0x200
+PLAN_MASK = PLAN_FWD | PLAN_BWD_INPUT | PLAN_SPATIAL
 ERR_CAPACITY = -2
 
 EXPORTS = ("pcpp_last_error", "pcpp_version", "pcpp_build_triplets_workspace_bytes",
@@ -53,18 +56,26 @@ def library() -> ctypes.CDLL:
                                       ctypes.POINTER(i64), vp, sz, i32, vp, sz, vp]
     L.pcpp_mvmr_workspace_bytes.restype = sz
     L.pcpp_mvmr_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
-    tail = [i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    head = [i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, sz, i32]     # sizes, triplets, plan
+    tail = head + [vp, sz, vp]                                             # workspace, stream
     L.pcpp_mvmr_fwd.restype = i32
     L.pcpp_mvmr_fwd.argtypes = [vp, vp, vp, i32, i32] + tail
     L.pcpp_mvmr_bwd_input.restype = i32
     L.pcpp_mvmr_bwd_input.argtypes = [vp, vp, vp, i32, i32] + tail
     L.pcpp_mvmr_bwd_weight.restype = i32
     L.pcpp_mvmr_bwd_weight.argtypes = [vp, vp, vp, i32] + tail
-    if hasattr(L, "pcpp_debug_set_list_cap"):
-        L.pcpp_debug_set_list_cap.restype = i32
-        L.pcpp_debug_set_list_cap.argtypes = [i32]
     _lib = L
     return L
+
+
+_landing = threading.local()
+
+
+def _landing_word():
+    """Pinned host word that pcpp_build_triplets lets the device write |T| into (one per host thread)."""
+    if getattr(_landing, "word", None) is None:
+        _landing.word = torch.zeros(8, dtype=torch.int64, pin_memory=True)
+    return _landing.word
 
 
 def _check(rc: int):
@@ -117,10 +128,11 @@ def pcpp_count_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
     n_in, n_out = in_xyz.shape[0], out_xyz.shape[0]
     ws_bytes = L.pcpp_build_triplets_workspace_bytes(n_in, n_out, t)
     ws = workspace if workspace is not None else _bytes(ws_bytes, in_xyz.device)
-    n = ctypes.c_int64(0)
+    n = _landing_word()
     _check(L.pcpp_build_triplets(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, float(radius), int(t), None, None, None,
-                                 0, None, ctypes.byref(n), None, 0, 0, _ptr(ws), ws.numel(), _stream()))
-    return int(n.value)
+                                 0, None, ctypes.cast(n.data_ptr(), ctypes.POINTER(ctypes.c_int64)), None, 0, 0,
+                                 _ptr(ws), ws.numel(), _stream()))
+    return int(n[0])
 
 
 def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: float, t: int,
@@ -128,10 +140,20 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
                         buffers: dict | None = None) -> Triplets:
     """Triplet construction (Sec. 3.2 with the fixed-radius search of Sec. 4.1) and reordering by (k, o, i).
 
-    in_xyz [n_in,3], out_xyz [n_out,3]: contiguous float32 CUDA tensors.  Without `capacity` the count is
-    taken first by a count-only call and the buffers are sized exactly.  `buffers` may carry preallocated
-    'tri_o','tri_i','tri_k','seg_offsets','plan','workspace' tensors to reuse.
+    in_xyz [n_in,3], out_xyz [n_out,3]: contiguous float32 CUDA tensors.  Without `capacity` room for 48
+    triplets per output point is provided; if that is too little the call reports the exact count and is
+    repeated once with it (so the search runs once in the common case).  `buffers` may carry preallocated
+    'tri_o','tri_i','tri_k','seg_offsets','plan','workspace' tensors to reuse.  plan_flags may include
+    PLAN_SPATIAL (tiles follow a space-filling order; for wide layers) and the BUILD_TEST_* aids.
     """
+    if capacity is None:
+        guess = max(48 * int(out_xyz.shape[0]), 1024)
+        try:
+            return pcpp_build_triplets(in_xyz, out_xyz, radius, t, plan_flags, guess, buffers)
+        except PcppError as e:
+            if e.code != ERR_CAPACITY:
+                raise
+            return pcpp_build_triplets(in_xyz, out_xyz, radius, t, plan_flags, e.needed, buffers)
     L = library()
     assert in_xyz.is_cuda and out_xyz.is_cuda and in_xyz.dtype == torch.float32 and out_xyz.dtype == torch.float32
     assert in_xyz.is_contiguous() and out_xyz.is_contiguous()
@@ -143,10 +165,6 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
     if ws_bytes == 0:
         raise PcppError(-1, "invalid sizes or t")
     ws = buffers.get("workspace")
-    if capacity is None:
-        if ws is None or ws.numel() < ws_bytes:
-            ws = _bytes(ws_bytes, dev)
-        capacity = pcpp_count_triplets(in_xyz, out_xyz, radius, t, ws)
     cap = max(int(capacity), 1)
     # room for the neighbour lists that let the second pass skip its search
     ws_bytes = max(ws_bytes, L.pcpp_build_triplets_workspace_bytes_for(n_in, n_out, t, cap))
@@ -161,20 +179,30 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
 
     tri_o, tri_i, tri_k = (buf(nm, cap, torch.int32) for nm in ("tri_o", "tri_i", "tri_k"))
     seg = buf("seg_offsets", K + 1, torch.int64)
-    plan_bytes = L.pcpp_plan_bytes(n_in, n_out, t, cap, plan_flags) if plan_flags else 0
+    want_plan = bool(plan_flags & PLAN_MASK)
+    plan_bytes = L.pcpp_plan_bytes(n_in, n_out, t, cap, plan_flags & PLAN_MASK) if want_plan else 0
     plan = buffers.get("plan")
-    if plan_flags and (plan is None or plan.numel() < plan_bytes):
+    if want_plan and (plan is None or plan.numel() < plan_bytes):
         plan = _bytes(plan_bytes, dev)
-    n = ctypes.c_int64(0)
+    n = _landing_word()
     rc = L.pcpp_build_triplets(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, float(radius), int(t),
-                               _ptr(tri_o), _ptr(tri_i), _ptr(tri_k), cap, _ptr(seg), ctypes.byref(n),
-                               _ptr(plan) if plan_flags else None, plan.numel() if plan_flags else 0, plan_flags,
+                               _ptr(tri_o), _ptr(tri_i), _ptr(tri_k), cap, _ptr(seg),
+                               ctypes.cast(n.data_ptr(), ctypes.POINTER(ctypes.c_int64)),
+                               _ptr(plan) if want_plan else None, plan.numel() if want_plan else 0, plan_flags,
                                _ptr(ws), ws.numel(), _stream())
+    nt = int(n[0])
     if rc == ERR_CAPACITY:
-        raise PcppError(rc, f"capacity {cap} too small, need {n.value}")
+        err = PcppError(rc, f"capacity {cap} too small, need {nt}")
+        err.needed = nt
+        raise err
     _check(rc)
-    nt = int(n.value)
-    return Triplets(tri_o[:nt], tri_i[:nt], tri_k[:nt], seg[:K + 1], nt, n_in, n_out, t, plan, plan_flags)
+    return Triplets(tri_o[:nt], tri_i[:nt], tri_k[:nt], seg[:K + 1], nt, n_in, n_out, t, plan, plan_flags & PLAN_MASK)
+
+
+def _plan_args(T: Triplets):
+    if T.plan is None:
+        return None, 0, T.plan_flags
+    return _ptr(T.plan), T.plan.numel(), T.plan_flags
 
 
 def _mvmr_ws(op, T: Triplets, c_in, c_out, code, dev, workspace):
@@ -196,7 +224,7 @@ def pcpp_mvmr_fwd(x: torch.Tensor, w: torch.Tensor, T: Triplets, out: torch.Tens
     ws = _mvmr_ws(0, T, c_in, c_out, _dtype_code(x), x.device, workspace)
     _check(L.pcpp_mvmr_fwd(_ptr(x), _ptr(w), _ptr(out), _dtype_code(x), _dtype_code(out), T.n_in, T.n_out, c_in, c_out,
                            K, _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets), T.n_triplets,
-                           _ptr(T.plan), _ptr(ws), ws.numel(), _stream()))
+                           *_plan_args(T), _ptr(ws), ws.numel(), _stream()))
     return out
 
 
@@ -214,7 +242,7 @@ def pcpp_mvmr_bwd_input(dy: torch.Tensor, w: torch.Tensor, T: Triplets, dx: torc
     ws = _mvmr_ws(1, T, c_in, c_out, _dtype_code(dy), dy.device, workspace)
     _check(L.pcpp_mvmr_bwd_input(_ptr(dy), _ptr(w), _ptr(dx), _dtype_code(dy), _dtype_code(dx), T.n_in, T.n_out, c_in,
                                  c_out, K, _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets),
-                                 T.n_triplets, _ptr(T.plan), _ptr(ws), ws.numel(), _stream()))
+                                 T.n_triplets, *_plan_args(T), _ptr(ws), ws.numel(), _stream()))
     return dx
 
 
@@ -230,5 +258,5 @@ def pcpp_mvmr_bwd_weight(x: torch.Tensor, dy: torch.Tensor, T: Triplets, dw: tor
     ws = _mvmr_ws(2, T, c_in, c_out, _dtype_code(x), x.device, workspace)
     _check(L.pcpp_mvmr_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), _dtype_code(x), T.n_in, T.n_out, c_in, c_out, T.K,
                                   _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets), T.n_triplets,
-                                  _ptr(T.plan), _ptr(ws), ws.numel(), _stream()))
+                                  *_plan_args(T), _ptr(ws), ws.numel(), _stream()))
     return dw

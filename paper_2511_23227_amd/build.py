@@ -19,6 +19,7 @@ SOURCES = {
     "pcpp_api.hip": [],
     "scan.hip": [],
     "build_triplets.hip": ["-ffp-contract=off"],
+    "spatial_order.hip": [],
     "mvmr_generic.hip": [],
     "mvmr_weight.hip": [],
     "mvmr_rows.hip": [],
@@ -26,7 +27,7 @@ SOURCES = {
     "mvmr_rows_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
-COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -82,10 +82,11 @@ __global__ __launch_bounds__(256) void grid_insert(const float *__restrict__ xyz
 __global__ __launch_bounds__(256) void grid_scatter(const float *__restrict__ xyz, int64_t n,
                                                     const uint32_t *__restrict__ point_slot,
                                                     const uint32_t *__restrict__ slot_start,
-                                                    uint32_t *__restrict__ cursor, float4 *__restrict__ pts)
+                                                    uint32_t *__restrict__ cursor, float4 *__restrict__ pts,
+                                                    const uint32_t *__restrict__ err)
 {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= n) return;
+    if (p >= n || *err) return;                       // err: the slot offsets come from a prefix sum that gave up
     const uint32_t slot = point_slot[p];
     const uint32_t pos = slot_start[slot] + atomicAdd(&cursor[slot], 1u);
     pts[pos] = make_float4(xyz[3 * p], xyz[3 * p + 1], xyz[3 * p + 2], __int_as_float((int)p));
@@ -231,8 +232,10 @@ struct CountOut {
 
 template <bool SWAP, bool BOTH>
 __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__restrict__ centres, int64_t n_centres,
+                                                              const int32_t *__restrict__ perm,
                                                               GridView g, QueryParams q, int K, int64_t n_tiles,
-                                                              CountOut side, CountOut mirror, uint32_t hit_stride)
+                                                              CountOut side, CountOut mirror, uint32_t hit_stride,
+                                                              const uint32_t *__restrict__ err)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE], with BOTH followed by the mirror side's [K][TILE]
     __shared__ uint32_t stage[(BOTH ? 2 : 1) * SEARCH_WAVES * KEEP_MAX];   // hit lists on their way to memory
@@ -240,14 +243,15 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
     const int64_t tile = blockIdx.x;
     uint32_t *tbl2 = tbl + K * TILE;
     uint32_t *mine = stage + wave * KEEP_MAX, *mine2 = stage + (SEARCH_WAVES + wave) * KEEP_MAX;
+    if (*err) return;                              // block-uniform: the grid's offsets are not to be trusted
     for (int idx = threadIdx.x; idx < (BOTH ? 2 : 1) * K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
     __syncthreads();
     const bool keep = side.hits != nullptr;
     for (int al = wave; al < TILE; al += SEARCH_WAVES) {
-        const int64_t a = tile * TILE + al;
+        const int64_t a = tile * TILE + al;        // slot; the tables and lists are indexed by it
         if (a >= n_centres) break;                 // wave-uniform
         Candidates<SWAP> c;
-        c.open(centres, a, g, lane);
+        c.open(centres, perm ? (int64_t)perm[a] : a, g, lane);
         uint32_t filled = 0;
         for (uint32_t base = 0; base < c.total; base += 64) {
             int b, k, k2;
@@ -299,30 +303,68 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
 // ---- pass 2: write every triplet to its place in (k, centre, other) order ----------------------
 //   tile_cnt  [n_tiles][K][TILE]  counts from pass 1
 //   tile_ptr  [K * n_tiles + 1]   exclusive prefix sum of tile_k_cnt
-//   out_c / out_b / out_k: centre index, candidate index, cell of each triplet (any may be NULL), out_cap entries each
-//                          (the pass is launched before the host has compared the count with the capacity)
+//   perm                          centre index of each slot (NULL: slots are centre indices); tables, lists and
+//                                 the centre's position in the order use the slot, coordinates and out_c the index
 // One wave per centre at a time.  The centre's neighbours are compacted into per-cell buckets of an
 // LDS list with wave ballots and prefix popcounts (the bucket sizes are the counts of pass 1), then
 // each neighbour's rank inside its bucket (number of smaller candidate indices) gives its final slot,
 // so ties between equal (k, centre) are ordered by the other index without any global sort.
 constexpr int KGROUPS = (MAX_K + 63) / 64;
 
+// Where the fill pass writes.  out_c / out_b / out_k: centre index, candidate index, cell of each triplet (any may
+// be NULL).  With tail_index >= 0 the candidate indices go to the tail_index-th |T|-sized array behind `tail`
+// instead (each align_up(|T| * 4) bytes, |T| read from the prefix sum's last entry), with GATHER_LAST set on the
+// last triplet of every run.  Nothing is written at or beyond position out_cap, and nothing at all when |T|
+// exceeds it (the pass is queued before the host has compared the count with what the caller provided).
+struct FillOut {
+    int32_t *out_c, *out_b, *out_k;
+    char *tail;
+    int tail_index;
+    uint32_t out_cap;
+};
+
+struct Emit {
+    int32_t *out_c, *out_b, *out_k;
+    const uint32_t *cnt_tile;
+    uint32_t cap;
+    bool flag_last;
+    __device__ inline void operator()(uint32_t run0, uint32_t rank, int al, int k, int32_t centre, uint32_t b) const
+    {
+        const uint32_t pos = run0 + rank;
+        if (pos >= cap) return;
+        if (out_c) out_c[pos] = centre;
+        if (out_b) out_b[pos] = (int32_t)((flag_last && rank + 1u == cnt_tile[k * TILE + al]) ? (b | GATHER_LAST) : b);
+        if (out_k) out_k[pos] = k;
+    }
+};
+
 template <bool SWAP>
 __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__restrict__ centres, int64_t n_centres,
+                                                             const int32_t *__restrict__ perm,
                                                              GridView g, QueryParams q, int K, int64_t n_tiles,
                                                              const uint32_t *__restrict__ tile_cnt,
                                                              const uint32_t *__restrict__ tile_ptr,
-                                                             int32_t *__restrict__ out_c, int32_t *__restrict__ out_b,
-                                                             int32_t *__restrict__ out_k,
+                                                             FillOut fo,
                                                              uint32_t *__restrict__ run_start_out, int list_cap,
                                                              const uint32_t *__restrict__ hits, uint32_t hit_stride,
-                                                             uint32_t out_cap, int64_t *__restrict__ seg_out,
-                                                             int pack_ok)
+                                                             int64_t *__restrict__ seg_out,
+                                                             int pack_ok, const uint32_t *__restrict__ err)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE]: start of each (k, centre) run, then [SEARCH_WAVES][K] bucket words
     __shared__ uint32_t list_all[SEARCH_WAVES][LIST_CAP_MAX];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
+    if (*err) return;                          // block-uniform: a prefix sum of this build gave up
+    const uint32_t total = tile_ptr[(size_t)K * n_tiles];
+    Emit emit;
+    emit.out_c = fo.out_c; emit.out_b = fo.out_b; emit.out_k = fo.out_k;
+    emit.cnt_tile = tile_cnt + (size_t)tile * K * TILE;
+    emit.cap = total <= fo.out_cap ? fo.out_cap : 0u;
+    emit.flag_last = false;
+    if (fo.tail_index >= 0) {
+        emit.out_b = reinterpret_cast<int32_t *>(fo.tail + (size_t)fo.tail_index * (((size_t)total * 4 + 255) / 256 * 256));
+        emit.flag_last = true;
+    }
     // start of every cell's segment (Sec. 3.3.2): the offset of its first tile; entry K is |T|
     if (seg_out && tile == 0)
         for (int k = threadIdx.x; k <= K; k += SEARCH_THREADS) seg_out[k] = (int64_t)tile_ptr[(size_t)k * n_tiles];
@@ -384,12 +426,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
             }
             if (l < (int)n) {
                 const int k = (int)(key >> HIT_INDEX_BITS);
-                const uint32_t pos = tbl[k * TILE + al] + rank;
-                if (pos < out_cap) {
-                    if (out_c) out_c[pos] = (int32_t)a;
-                    if (out_b) out_b[pos] = (int32_t)rel;
-                    if (out_k) out_k[pos] = k;
-                }
+                emit(tbl[k * TILE + al], rank, al, k, (int32_t)(perm ? (int64_t)perm[a] : a), rel);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -399,9 +436,10 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
         const int al = wave + u * SEARCH_WAVES;
-        const int64_t a = tile * TILE + al;
+        const int64_t a = tile * TILE + al;    // slot
         if (a >= n_centres) break;             // wave-uniform
         if (n_of[u] == 0) continue;            // wave-uniform
+        const int32_t ac = (int32_t)(perm ? (int64_t)perm[a] : a);   // the centre's own index
         if (pack_ok && n_of[u] > BUCKET_FROM && n_of[u] <= (uint32_t)list_cap) {
             // Longer lists, when cell and candidate index fit one word (cell << 24 | index).  The keys -- read back from the count pass
             // when it kept them, found again otherwise -- are dropped into per-cell buckets of the list through one
@@ -429,7 +467,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                 }
             } else {
                 Candidates<SWAP> &c = cand[0];
-                c.open(centres, a, g, lane);
+                c.open(centres, ac, g, lane);
                 for (uint32_t base = 0; base < c.total; base += 64) {
                     int b, k;
                     if (c.fetch(base + lane, g, q, b, k)) {
@@ -452,14 +490,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                     const uint32_t v = j < nk ? list[b0 + j] : 0xffffffffu;
                     rank += v < key ? 1u : 0u;
                 }
-                if (have) {
-                    const uint32_t pos = tbl[k * TILE + al] + rank;
-                    if (pos < out_cap) {
-                        if (out_c) out_c[pos] = (int32_t)a;
-                        if (out_b) out_b[pos] = (int32_t)(key & HIT_INDEX_MASK);
-                        if (out_k) out_k[pos] = k;
-                    }
-                }
+                if (have) emit(tbl[k * TILE + al], rank, al, k, ac, key & HIT_INDEX_MASK);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -485,12 +516,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                 }
                 for (; e2 < n; ++e2) rank += (list[e2] - kbase) < rel ? 1u : 0u;
                 const int k = (int)(key >> HIT_INDEX_BITS);
-                const uint32_t pos = tbl[k * TILE + al] + rank;
-                if (pos < out_cap) {
-                    if (out_c) out_c[pos] = (int32_t)a;
-                    if (out_b) out_b[pos] = (int32_t)rel;
-                    if (out_k) out_k[pos] = k;
-                }
+                emit(tbl[k * TILE + al], rank, al, k, ac, rel);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -512,7 +538,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
         }
         if (n == 0) continue;                  // wave-uniform
         Candidates<SWAP> &c = cand[0];
-        c.open(centres, a, g, lane);
+        c.open(centres, ac, g, lane);
         if (n <= SMALL_LIST && n <= (uint32_t)list_cap) {
             // few neighbours: one flat list of (cell, index) keys in arrival order, rank by comparing all pairs
             unsigned long long *keys = reinterpret_cast<unsigned long long *>(list);
@@ -540,12 +566,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                 }
                 for (; e2 < n; ++e2) rank += ((keys[e2] - kbase) < rel) ? 1u : 0u;
                 const int k = (int)(key >> 32);
-                const uint32_t pos = tbl[k * TILE + al] + rank;
-                if (pos < out_cap) {
-                    if (out_c) out_c[pos] = (int32_t)a;
-                    if (out_b) out_b[pos] = (int32_t)(uint32_t)key;
-                    if (out_k) out_k[pos] = k;
-                }
+                emit(tbl[k * TILE + al], rank, al, k, ac, (uint32_t)key);
             }
         } else if (n <= (uint32_t)list_cap) {
             for (uint32_t base = 0; base < c.total; base += 64) {
@@ -591,12 +612,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                             for (int u = 0; u < 8; ++u) rank += v[u] < mine ? 1u : 0u;
                         }
                         for (; e2 < nk; ++e2) rank += list[b0 + e2] < mine ? 1u : 0u;
-                        if (e < nk && run0 + rank < out_cap) {
-                            const uint32_t pos = run0 + rank;
-                            if (out_c) out_c[pos] = (int32_t)a;
-                            if (out_b) out_b[pos] = (int32_t)mine;
-                            if (out_k) out_k[pos] = k;
-                        }
+                        if (e < nk) emit(run0, rank, al, k, ac, mine);
                     }
                 }
             }
@@ -611,12 +627,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                     const bool hit2 = c.fetch(idx2, g, q, b2, k2);
                     rank += (hit2 && k2 == k && b2 < b) ? 1u : 0u;
                 }
-                if (hit && tbl[k * TILE + al] + rank < out_cap) {
-                    const uint32_t pos = tbl[k * TILE + al] + rank;
-                    if (out_c) out_c[pos] = (int32_t)a;
-                    if (out_b) out_b[pos] = b;
-                    if (out_k) out_k[pos] = k;
-                }
+                if (hit) emit(tbl[k * TILE + al], rank, al, k, ac, (uint32_t)b);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -652,14 +663,21 @@ GridScratch grid_scratch(size_t base, int64_t n)
     return s;
 }
 
-constexpr int N_SCANS = 4;           // prefix sums of one build, each with status words of its own
+// prefix sums of one build, each with status words of its own: the two grids, the public (k, o, i) list, the
+// two sides of a spatial plan (or the input-gradient side of a plain one), and the passes of two spatial sorts
+constexpr int SCAN_GRID_IN = 0, SCAN_GRID_OUT = 1, SCAN_PUBLIC = 2, SCAN_FWD_SIDE = 3, SCAN_BWD_SIDE = 4,
+              SCAN_SORT_OUT = 5, SCAN_SORT_IN = SCAN_SORT_OUT + SPATIAL_ORDER_SCANS,
+              N_SCANS = SCAN_SORT_IN + SPATIAL_ORDER_SCANS;
 
 struct BuildScratch {
     GridScratch grid_in, grid_out;
+    size_t err_off;                  // one word: raised by a prefix sum whose wait ran out
+    size_t total_off;                // |T| as the prefix sum leaves it, when the caller's landing word is pageable
     size_t scan_off;                 // status words of the prefix sums: N_SCANS regions of scan_stride bytes
     size_t scan_stride;
-    size_t fwd_ptr_off, fwd_cnt_off; // used when the caller gives no plan
+    size_t fwd_ptr_off, fwd_cnt_off; // per-(k, tile) sums / offsets and per-(k, centre) counts of the pass in flight
     size_t bwd_ptr_off, bwd_cnt_off;
+    size_t sort_off;                 // scratch of the spatial sorts
     size_t end;                      // without hit lists
     // Optional, after `end`: the first hit_stride neighbours of every centre as found by the count pass, so
     // that the fill pass need not search again (needs the triplet capacity to size the lists).
@@ -687,12 +705,17 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity 
     int64_t scan_n = b.grid_in.slots > b.grid_out.slots ? b.grid_in.slots : b.grid_out.slots;
     if ((int64_t)K * nt_o > scan_n) scan_n = (int64_t)K * nt_o;
     if ((int64_t)K * nt_i > scan_n) scan_n = (int64_t)K * nt_i;
+    const int64_t n_max = n_in > n_out ? n_in : n_out;
+    if (spatial_order_scan_items(n_max) > scan_n) scan_n = spatial_order_scan_items(n_max);
+    b.err_off = off;     off += 256;
+    b.total_off = off;   off += 256;
     b.scan_stride = scan_scratch_bytes(scan_n);
     b.scan_off = off;    off += N_SCANS * b.scan_stride;
     b.fwd_ptr_off = off; off += align_up((size_t)(K * nt_o + 1) * 4);
     b.fwd_cnt_off = off; off += align_up((size_t)(nt_o > 0 ? nt_o : 1) * K * TILE * 4);
     b.bwd_ptr_off = off; off += align_up((size_t)(K * nt_i + 1) * 4);
     b.bwd_cnt_off = off; off += align_up((size_t)(nt_i > 0 ? nt_i : 1) * K * TILE * 4);
+    b.sort_off = off;    off += spatial_order_scratch_bytes(n_max);
     b.end = off;
     b.end_with_hits = off;
     // stored hits carry the candidate index in HIT_INDEX_BITS bits
@@ -706,10 +729,11 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity 
     return b;
 }
 
-// scan_scratch: the status words of this grid's prefix sum; clear_words > 0: the status words of all the
-// build's prefix sums start at scan_scratch and are zeroed here
+// scan_scratch: the status words of this grid's prefix sum.  clear_words > 0: the first grid of a build, whose
+// clearing kernel also zeroes the error word and the status words of all the build's prefix sums (they follow
+// the error word in the workspace).
 int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridScratch &gs, void *scan_scratch,
-               int64_t clear_words, GridView *view, hipStream_t stream)
+               unsigned long long *clear_from, int64_t clear_words, uint32_t *err, GridView *view, hipStream_t stream)
 {
     auto *keys = reinterpret_cast<unsigned long long *>(ws + gs.keys_off);
     auto *cnt = reinterpret_cast<uint32_t *>(ws + gs.cnt_off);
@@ -720,8 +744,7 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
     {
         int64_t blocks = ceil_div(gs.slots + 1, 256);
         if (blocks > 4096) blocks = 4096;
-        grid_clear<<<(unsigned)blocks, 256, 0, stream>>>(keys, cnt, cursor, gs.slots,
-                                                         static_cast<unsigned long long *>(scan_scratch), clear_words);
+        grid_clear<<<(unsigned)blocks, 256, 0, stream>>>(keys, cnt, cursor, gs.slots, clear_from, clear_words);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if (n > 0) {
@@ -729,10 +752,10 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
         grid_insert<<<blocks, 256, 0, stream>>>(xyz, n, inv_g, keys, cnt, (uint32_t)(gs.slots - 1), point_slot);
         PCPP_HIP_CHECK(hipGetLastError());
     }
-    if ((rc = scan_exclusive_u32(cnt, cnt, gs.slots, scan_scratch, nullptr, stream)) != PCPP_OK) return rc;
+    if ((rc = scan_exclusive_u32(cnt, cnt, gs.slots, scan_scratch, nullptr, err, stream)) != PCPP_OK) return rc;
     if (n > 0) {
         const unsigned blocks = (unsigned)ceil_div(n, 256);
-        grid_scatter<<<blocks, 256, 0, stream>>>(xyz, n, point_slot, cnt, cursor, pts);
+        grid_scatter<<<blocks, 256, 0, stream>>>(xyz, n, point_slot, cnt, cursor, pts, err);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     view->keys = keys;
@@ -743,38 +766,35 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
     return PCPP_OK;
 }
 
-int g_list_cap = LIST_CAP_MAX;
-
-// Per host thread: pinned landing place of |T| and the event that says it has arrived.  Created on first use
-// and kept until the process ends.
-struct HostTotal {
-    unsigned long long *pinned = nullptr;
-    hipEvent_t ready = nullptr;
+// The event that tells the host that |T| has landed; created and destroyed inside one call.
+struct CallEvent {
+    hipEvent_t ev = nullptr;
+    ~CallEvent() { if (ev) (void)hipEventDestroy(ev); }
 };
-HostTotal &host_total()
-{
-    static thread_local HostTotal t;
-    return t;
-}
 
 }  // namespace
 
 PlanLayout plan_layout(int64_t n_in, int64_t n_out, int K, int64_t n_triplets, int flags)
 {
     PlanLayout p;
-    size_t off = 256;   // header
+    const bool spatial = (flags & PCPP_PLAN_SPATIAL) != 0;
+    size_t off = 256;   // header (reserved)
     auto side = [&](SideLayout &s, int64_t n_centres, bool with_gather) {
         s.n_centres = n_centres;
         s.n_tiles = ceil_div(n_centres, TILE);
+        s.perm_off = off;
+        if (spatial) off += align_up((size_t)(n_centres > 0 ? n_centres : 1) * 4);
         s.tile_ptr_off = off;  off += align_up((size_t)(K * s.n_tiles + 1) * 4);
         s.run_start_off = off; off += align_up((size_t)(s.n_tiles > 0 ? s.n_tiles : 1) * K * TILE * 4);
-        s.gather_off = off;
-        if (with_gather) off += align_up((size_t)(n_triplets > 0 ? n_triplets : 1) * 4);
-        s.end = off;
+        if (with_gather) s.gather_index = p.n_tail++;
     };
-    if (flags & PCPP_PLAN_FWD) side(p.fwd, n_out, false);
+    if (flags & PCPP_PLAN_FWD) side(p.fwd, n_out, spatial);
     if (flags & PCPP_PLAN_BWD_INPUT) side(p.bwd, n_in, true);
-    p.bytes = off;
+    p.tail_off = off;
+    const size_t each = align_up((size_t)(n_triplets > 0 ? n_triplets : 1) * 4);
+    if (p.fwd.gather_index >= 0) p.fwd.gather_off = off + (size_t)p.fwd.gather_index * each;
+    if (p.bwd.gather_index >= 0) p.bwd.gather_off = off + (size_t)p.bwd.gather_index * each;
+    p.bytes = off + (size_t)p.n_tail * each;
     return p;
 }
 
@@ -799,16 +819,7 @@ size_t pcpp_build_triplets_workspace_bytes_for(int64_t n_in, int64_t n_out, int 
 size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags)
 {
     if (n_in < 0 || n_out < 0 || t < 1 || t > PCPP_MAX_T || n_triplets < 0) return 0;
-    return plan_layout(n_in, n_out, t * t * t, n_triplets, plan_flags).bytes;
-}
-
-// Test hook: number of neighbours of one centre the fill pass keeps on chip before it falls back to
-// ranking by a second scan of the candidates (1..512).  Not part of the public contract.
-int pcpp_debug_set_list_cap(int cap)
-{
-    if (cap < 1 || cap > LIST_CAP_MAX) return PCPP_ERR_INVALID_ARG;
-    g_list_cap = cap;
-    return PCPP_OK;
+    return plan_layout(n_in, n_out, t * t * t, n_triplets, plan_flags & PLAN_FLAG_MASK).bytes;
 }
 
 int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz, int64_t n_out,
@@ -845,8 +856,14 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         set_error("pcpp_build_triplets: seg_offsets is NULL or capacity negative");
         return PCPP_ERR_INVALID_ARG;
     }
-    if (plan && ((plan_flags & ~(PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT)) || !(plan_flags & PCPP_PLAN_FWD))) {
-        set_error("pcpp_build_triplets: plan_flags must be PCPP_PLAN_FWD, optionally with PCPP_PLAN_BWD_INPUT");
+    const int test_flags = plan_flags & (PCPP_BUILD_TEST_SHORT_LISTS | PCPP_BUILD_TEST_WIDE_KEYS);
+    if (plan_flags & ~(PLAN_FLAG_MASK | PCPP_BUILD_TEST_SHORT_LISTS | PCPP_BUILD_TEST_WIDE_KEYS)) {
+        set_error("pcpp_build_triplets: unknown bits in plan_flags");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    plan_flags &= PLAN_FLAG_MASK;
+    if (plan && !(plan_flags & PCPP_PLAN_FWD)) {
+        set_error("pcpp_build_triplets: plan_flags must include PCPP_PLAN_FWD");
         return PCPP_ERR_INVALID_ARG;
     }
     const int K = t * t * t;
@@ -861,11 +878,29 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     }
     *n_triplets = 0;
     char *ws = static_cast<char *>(workspace);
-    const bool keep_hits = bs.fwd_stride != 0 && workspace_bytes >= bs.end_with_hits;
+    const bool wide_keys = (test_flags & PCPP_BUILD_TEST_WIDE_KEYS) != 0;
+    const bool keep_hits = bs.fwd_stride != 0 && workspace_bytes >= bs.end_with_hits && !wide_keys;
     uint32_t *f_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.fwd_hits_off) : nullptr;
     uint32_t *b_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.bwd_hits_off) : nullptr;
-    // one set of status words per prefix sum: candidates' grid, forward counts, centres' grid, swapped counts
+    uint32_t *err = reinterpret_cast<uint32_t *>(ws + bs.err_off);
     auto scan_scratch = [&](int which) -> void * { return ws + bs.scan_off + (size_t)which * bs.scan_stride; };
+    const int list_cap = (test_flags & PCPP_BUILD_TEST_SHORT_LISTS) ? 40 : LIST_CAP_MAX;
+
+    // Where |T| lands.  Pinned host memory is written by the device itself (the prefix sum's last block), so the
+    // host can pick the count up while the second pass is already running; pageable memory gets it through a
+    // blocking copy before that pass is queued.
+    unsigned long long *total_dev = reinterpret_cast<unsigned long long *>(ws + bs.total_off);
+    bool pinned = false;
+    {
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, n_triplets) == hipSuccess && attr.type == hipMemoryTypeHost &&
+            attr.devicePointer) {
+            total_dev = static_cast<unsigned long long *>(attr.devicePointer);
+            pinned = true;
+        } else {
+            (void)hipGetLastError();                 // an unregistered pointer is reported as an error; it is not one
+        }
+    }
 
     // grid pitch a hair above r so that, with the binary64 cell computation, any accepted pair lies
     // in adjacent grid cells (27-cell stencil is conservative)
@@ -879,81 +914,92 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
 
     int rc;
     GridView grid_in;
-    if ((rc = build_grid(in_xyz, n_in, inv_g, ws, bs.grid_in, scan_scratch(0),
-                         (int64_t)(N_SCANS * bs.scan_stride / sizeof(unsigned long long)), &grid_in, stream)) != PCPP_OK) return rc;
+    // the clearing kernel of the first grid zeroes the error word, the total and all status words (contiguous)
+    if ((rc = build_grid(in_xyz, n_in, inv_g, ws, bs.grid_in, scan_scratch(SCAN_GRID_IN),
+                         reinterpret_cast<unsigned long long *>(ws + bs.err_off),
+                         (int64_t)((512 + N_SCANS * bs.scan_stride) / sizeof(unsigned long long)), err, &grid_in,
+                         stream)) != PCPP_OK)
+        return rc;
 
-    const int64_t nt_o = ceil_div(n_out, TILE);
+    const int64_t nt_o = ceil_div(n_out, TILE), nt_i = ceil_div(n_in, TILE);
     const size_t lds = (size_t)K * TILE * sizeof(uint32_t);
     // the second pass also keeps one bucket word per (wave, cell); a key packs cell and candidate index into 32 bits
     const size_t lds_fill = lds + (size_t)SEARCH_WAVES * K * sizeof(uint32_t);
-    const int pack_ok = K <= 256 && n_in < (1 << HIT_INDEX_BITS) && n_out < (1 << HIT_INDEX_BITS);
+    const int pack_ok = !wide_keys && K <= 256 && n_in < (1 << HIT_INDEX_BITS) && n_out < (1 << HIT_INDEX_BITS);
     if (lds > (size_t)32 * 1024) {
         // large t: the per-tile table plus the neighbour lists exceed the default dynamic LDS limit
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<true, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_count<false, false>), lds)) != PCPP_OK) return rc;
+        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_count<true, false>), lds)) != PCPP_OK) return rc;
     }
     if (lds_fill > (size_t)32 * 1024) {
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fill));
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_fill<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fill));
+        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_fill<false>), lds_fill)) != PCPP_OK) return rc;
+        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_fill<true>), lds_fill)) != PCPP_OK) return rc;
     }
-    const bool want_fwd_plan = plan && (plan_flags & PCPP_PLAN_FWD) && !count_only;
-    const bool want_bwd_plan = plan && (plan_flags & PCPP_PLAN_BWD_INPUT) && !count_only;
+    const bool want_plan = plan && !count_only;
+    const bool want_bwd = want_plan && (plan_flags & PCPP_PLAN_BWD_INPUT);
+    const bool spatial = want_plan && (plan_flags & PCPP_PLAN_SPATIAL);
+    const bool self = out_xyz == in_xyz && n_out == n_in;
 
-    // forward side: centres = outputs, candidates = inputs.  Counts go to the workspace first; the
-    // plan layout depends on |T|, which is only known after the prefix sum.
-    uint32_t *f_ptr = reinterpret_cast<uint32_t *>(ws + bs.fwd_ptr_off);
-    uint32_t *f_cnt = reinterpret_cast<uint32_t *>(ws + bs.fwd_cnt_off);
-    // A cloud queried against itself: one pass counts both sides (while two [K][64] tables fit beside the lists
-    // in the LDS share of two blocks per CU, and within what one block may allocate on this device).
-    bool one_pass = want_bwd_plan && out_xyz == in_xyz && n_out == n_in && 2 * lds <= (size_t)72 * 1024;
+    // A cloud queried against itself: one pass counts both sides of the plan (while two [K][64] tables fit the
+    // LDS that one block may allocate, beside the lists).
+    bool one_pass = want_bwd && self && 2 * lds <= (size_t)72 * 1024;
     if (one_pass && 2 * lds > (size_t)32 * 1024) {
         int dev = 0, per_block = 0;
         PCPP_HIP_CHECK(hipGetDevice(&dev));
         PCPP_HIP_CHECK(hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
         if (2 * lds + (size_t)2 * SEARCH_WAVES * KEEP_MAX * sizeof(uint32_t) + 1024 > (size_t)per_block) one_pass = false;
-        else
-            PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&query_count<false, true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * lds)));
+        else if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_count<false, true>), 2 * lds)) != PCPP_OK)
+            return rc;
     }
-    uint32_t *b_cnt = reinterpret_cast<uint32_t *>(ws + bs.bwd_cnt_off);
-    uint32_t *b_sum = reinterpret_cast<uint32_t *>(ws + bs.bwd_ptr_off);   // per-(k, tile) sums of the swapped side
-    if (nt_o > 0) {
-        const CountOut fwd_out{count_only ? nullptr : f_cnt, f_ptr, f_hits};
-        if (one_pass)
-            query_count<false, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
-                out_xyz, n_out, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride);
-        else
-            query_count<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
-                out_xyz, n_out, grid_in, q, K, nt_o, fwd_out, CountOut{nullptr, nullptr, nullptr}, bs.fwd_stride);
-        PCPP_HIP_CHECK(hipGetLastError());
-    }
-    // the offsets inside the plan do not depend on |T| (the only array that does comes last)
-    const PlanLayout pl = (plan && !count_only) ? plan_layout(n_in, n_out, K, 0, plan_flags) : PlanLayout{};
-    if (plan && !count_only && plan_bytes < pl.bytes) {
+
+    // the offsets of everything but the |T|-sized arrays do not depend on |T|
+    const PlanLayout pl = want_plan ? plan_layout(n_in, n_out, K, 0, plan_flags) : PlanLayout{};
+    if (want_plan && plan_bytes < pl.bytes) {
         set_error("pcpp_build_triplets: plan buffer has %zu bytes, needs at least %zu", plan_bytes, pl.bytes);
         return PCPP_ERR_WORKSPACE;
     }
     char *pb = static_cast<char *>(plan);
-    // the tile offsets go straight into the plan when one is wanted
-    uint32_t *f_off = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.tile_ptr_off) : f_ptr;
+    uint32_t *f_ptr = reinterpret_cast<uint32_t *>(ws + bs.fwd_ptr_off);
+    uint32_t *f_cnt = reinterpret_cast<uint32_t *>(ws + bs.fwd_cnt_off);
+    uint32_t *b_cnt = reinterpret_cast<uint32_t *>(ws + bs.bwd_cnt_off);
+    uint32_t *b_sum = reinterpret_cast<uint32_t *>(ws + bs.bwd_ptr_off);   // per-(k, tile) sums of the swapped side
+    const CountOut none{nullptr, nullptr, nullptr};
+    // the plan's own tables, when the first pass already runs in the plan's order (a plain plan)
+    const bool fwd_direct = want_plan && !spatial;
+    uint32_t *f_off = fwd_direct ? reinterpret_cast<uint32_t *>(pb + pl.fwd.tile_ptr_off) : f_ptr;
 
-    // |T| is written by the prefix sum into pinned host memory, with an event behind it, so that the host can
-    // pick it up while the second pass is already running; that pass guards its writes with the capacities
-    // instead of waiting for the check.
-    HostTotal &ht = host_total();
-    if (!ht.pinned) {
-        PCPP_HIP_CHECK(hipHostMalloc(reinterpret_cast<void **>(&ht.pinned), 64, hipHostMallocDefault));
-        PCPP_HIP_CHECK(hipEventCreateWithFlags(&ht.ready, hipEventDisableTiming));
+    // ---- the public list: centres = outputs in index order, candidates = inputs ------------------------------
+    if (nt_o > 0) {
+        const CountOut fwd_out{count_only ? nullptr : f_cnt, f_ptr, f_hits};
+        if (one_pass && !spatial)
+            query_count<false, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+        else
+            query_count<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+        PCPP_HIP_CHECK(hipGetLastError());
     }
-    if ((rc = scan_exclusive_u32(f_ptr, f_off, (int64_t)K * nt_o, scan_scratch(1), ht.pinned, stream)) != PCPP_OK) return rc;
-    PCPP_HIP_CHECK(hipEventRecord(ht.ready, stream));
-    auto wait_total = [&](unsigned long long &total) -> int {
-        PCPP_HIP_CHECK(hipEventSynchronize(ht.ready));
-        total = *ht.pinned;
+    if ((rc = scan_exclusive_u32(f_ptr, f_off, (int64_t)K * nt_o, scan_scratch(SCAN_PUBLIC), total_dev, err, stream)) != PCPP_OK)
+        return rc;
+    CallEvent landed;
+    unsigned long long total = 0;
+    bool have_total = false;
+    auto wait_total = [&]() -> int {
+        if (!have_total) {
+            if (pinned) {
+                PCPP_HIP_CHECK(hipEventSynchronize(landed.ev));
+                total = *reinterpret_cast<volatile unsigned long long *>(n_triplets);
+            } else {
+                PCPP_HIP_CHECK(hipMemcpyAsync(&total, total_dev, sizeof(total), hipMemcpyDeviceToHost, stream));
+                PCPP_HIP_CHECK(hipStreamSynchronize(stream));
+            }
+            have_total = true;
+        }
+        if (total == ~0ull) {
+            *n_triplets = 0;
+            set_error("pcpp_build_triplets: a wait inside a device-wide prefix sum ran out");
+            return PCPP_ERR_HIP;
+        }
         *n_triplets = (int64_t)total;
         if (total >= (unsigned long long)INT32_MAX) {
             set_error("pcpp_build_triplets: %llu triplets; the library indexes at most 2^31-1", total);
@@ -961,55 +1007,102 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         }
         return PCPP_OK;
     };
-    unsigned long long total = 0;
-    if (count_only) return wait_total(total);
+    if (pinned) {
+        PCPP_HIP_CHECK(hipEventCreateWithFlags(&landed.ev, hipEventDisableTiming));
+        PCPP_HIP_CHECK(hipEventRecord(landed.ev, stream));
+    } else if ((rc = wait_total()) != PCPP_OK) {
+        return rc;
+    }
+    if (count_only) return wait_total();
 
     const uint32_t tri_cap = (uint32_t)(capacity < (int64_t)INT32_MAX ? capacity : (int64_t)INT32_MAX);
+    // how many triplets the |T|-sized arrays of the plan have room for
+    uint32_t tail_cap = 0;
+    if (want_plan && pl.n_tail > 0) {
+        const size_t room = (plan_bytes - pl.tail_off) / (size_t)pl.n_tail / 256 * 256 / 4;
+        tail_cap = (uint32_t)(room < (size_t)tri_cap ? room : (size_t)tri_cap);
+    }
     if (nt_o > 0) {
-        uint32_t *f_runs = want_fwd_plan ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
-        query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(out_xyz, n_out, grid_in, q, K, nt_o, f_cnt,
-                                                                        f_off, tri_o, tri_i, tri_k, f_runs,
-                                                                        g_list_cap, f_hits, bs.fwd_stride, tri_cap,
-                                                                        seg_offsets, pack_ok);
+        uint32_t *f_runs = fwd_direct ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
+        query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
+            out_xyz, n_out, nullptr, grid_in, q, K, nt_o, f_cnt, f_off, FillOut{tri_o, tri_i, tri_k, nullptr, -1, tri_cap},
+            f_runs, list_cap, f_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
         PCPP_HIP_CHECK(hipGetLastError());
     } else {
         // no outputs: every run starts at 0
-        PCPP_HIP_CHECK(hipMemsetAsync(seg_offsets, 0, (size_t)(K + 1) * sizeof(int64_t), stream));
+        if ((rc = fill_u64(reinterpret_cast<unsigned long long *>(seg_offsets), 0ull, K + 1, stream)) != PCPP_OK) return rc;
     }
-    if (want_bwd_plan) {
-        // input-gradient side: centres = inputs, candidates = outputs; same predicate with the roles
-        // swapped, so the set is identical and only the grouping changes to (k, i, o)
-        const int64_t nt_i = ceil_div(n_in, TILE);
-        GridView grid_out;
-        if (out_xyz == in_xyz && n_out == n_in) {
-            grid_out = grid_in;
-        } else {
-            if ((rc = build_grid(out_xyz, n_out, inv_g, ws, bs.grid_out, scan_scratch(2), 0, &grid_out, stream)) != PCPP_OK)
+
+    // ---- the plan's sides ---------------------------------------------------------------------------------------
+    GridView grid_out = grid_in;
+    if (want_bwd && !self) {
+        if ((rc = build_grid(out_xyz, n_out, inv_g, ws, bs.grid_out, scan_scratch(SCAN_GRID_OUT), nullptr, 0, err,
+                             &grid_out, stream)) != PCPP_OK)
+            return rc;
+    }
+    const int32_t *perm_o = nullptr, *perm_i = nullptr;
+    if (spatial) {
+        // cells of half the radius: a tile of 64 centres then spans a few radii at the densities the layers see
+        const double pitch = 0.5 * R;
+        int32_t *po = reinterpret_cast<int32_t *>(pb + pl.fwd.perm_off);
+        if ((rc = spatial_order(out_xyz, n_out, pitch, po, ws + bs.sort_off, scan_scratch(SCAN_SORT_OUT), bs.scan_stride,
+                                err, stream)) != PCPP_OK)
+            return rc;
+        perm_o = po;
+        if (want_bwd) {
+            int32_t *pi = reinterpret_cast<int32_t *>(pb + pl.bwd.perm_off);
+            if (self) {
+                PCPP_HIP_CHECK(hipMemcpyAsync(pi, po, (size_t)n_in * 4, hipMemcpyDeviceToDevice, stream));
+            } else if ((rc = spatial_order(in_xyz, n_in, pitch, pi, ws + bs.sort_off, scan_scratch(SCAN_SORT_IN),
+                                           bs.scan_stride, err, stream)) != PCPP_OK) {
                 return rc;
+            }
+            perm_i = pi;
         }
-        uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
-        uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
-        int32_t *b_gather = reinterpret_cast<int32_t *>(pb + pl.bwd.gather_off);
-        const size_t gather_room = (plan_bytes - pl.bwd.gather_off) / 4;
-        const uint32_t gather_cap = (uint32_t)(gather_room < (size_t)tri_cap ? gather_room : (size_t)tri_cap);
-        if (nt_i > 0 && !one_pass) {
-            query_count<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
-                in_xyz, n_in, grid_out, q, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, CountOut{nullptr, nullptr, nullptr},
-                bs.bwd_stride);
+        // forward side in the spatial order: same search, centres taken through the permutation
+        uint32_t *sf_ptr = reinterpret_cast<uint32_t *>(pb + pl.fwd.tile_ptr_off);
+        if (nt_o > 0) {
+            const CountOut fwd_out{f_cnt, f_ptr, f_hits};
+            if (one_pass)
+                query_count<false, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+            else
+                query_count<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
             PCPP_HIP_CHECK(hipGetLastError());
         }
-        if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch(3), nullptr, stream)) != PCPP_OK)
+        if ((rc = scan_exclusive_u32(f_ptr, sf_ptr, (int64_t)K * nt_o, scan_scratch(SCAN_FWD_SIDE), nullptr, err, stream)) != PCPP_OK)
+            return rc;
+        if (nt_o > 0) {
+            query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
+                out_xyz, n_out, perm_o, grid_in, q, K, nt_o, f_cnt, sf_ptr,
+                FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.fwd.gather_index, tail_cap},
+                reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off), list_cap, f_hits, bs.fwd_stride, nullptr, pack_ok, err);
+            PCPP_HIP_CHECK(hipGetLastError());
+        }
+    }
+    if (want_bwd) {
+        // input-gradient side: centres = inputs, candidates = outputs; same predicate with the roles
+        // swapped, so the set is identical and only the grouping changes to (k, i, o)
+        uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
+        uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
+        if (nt_i > 0 && !one_pass) {
+            query_count<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
+                in_xyz, n_in, perm_i, grid_out, q, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
+            PCPP_HIP_CHECK(hipGetLastError());
+        }
+        if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch(SCAN_BWD_SIDE), nullptr, err, stream)) != PCPP_OK)
             return rc;
         if (nt_i > 0) {
-            query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(in_xyz, n_in, grid_out, q, K, nt_i, b_cnt,
-                                                                           b_ptr, nullptr, b_gather, nullptr, b_runs,
-                                                                           g_list_cap, b_hits, bs.bwd_stride, gather_cap,
-                                                                           nullptr, pack_ok);
+            query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(
+                in_xyz, n_in, perm_i, grid_out, q, K, nt_i, b_cnt, b_ptr,
+                FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.bwd.gather_index, tail_cap}, b_runs, list_cap,
+                b_hits, bs.bwd_stride, nullptr, pack_ok, err);
             PCPP_HIP_CHECK(hipGetLastError());
         }
     }
     // everything is queued; now compare the count with what the caller provided
-    if ((rc = wait_total(total)) != PCPP_OK) return rc;
+    if ((rc = wait_total()) != PCPP_OK) return rc;
     if ((int64_t)total > capacity) {
         set_error("pcpp_build_triplets: %llu triplets but capacity is %lld", total, (long long)capacity);
         return PCPP_ERR_CAPACITY;

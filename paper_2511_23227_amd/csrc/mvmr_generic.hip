@@ -59,7 +59,7 @@ __device__ inline void presum_chunk(const T *__restrict__ feat, int c_src, int c
     for (int e = 0; e < 16; ++e) s[e] = 0.f;
     const uint32_t n = row_cnt[r], st = row_start[r];
     for (uint32_t j = 0; j < n; ++j) {
-        const size_t row = (size_t)gather[st + j] * c_src;
+        const size_t row = (size_t)((uint32_t)gather[st + j] & GATHER_INDEX) * c_src;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int c = c0 + q * 16 + e;
@@ -116,8 +116,9 @@ __global__ __launch_bounds__(THREADS) void rows_kernel(const TIn *__restrict__ f
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int64_t row = tile * TILE + rg * 4 + i;
-        if (row >= n_centres) continue;
+        const int64_t slot = tile * TILE + rg * 4 + i;
+        if (slot >= n_centres) continue;
+        const int64_t row = side.perm ? (int64_t)side.perm[slot] : slot;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int co = d0 + cg + 16 * j;
@@ -162,12 +163,13 @@ __global__ __launch_bounds__(THREADS) void weight_kernel(const T *__restrict__ f
         presum_chunk<T>(feat, c_in, ci0, gather, row_start, row_cnt, S);
         {
             const int r = threadIdx.x >> 2, q = threadIdx.x & 3;
-            const int64_t row = tile * TILE + r;
+            const int64_t slot = tile * TILE + r;
+            const int64_t row = (slot < n_centres && side.perm) ? (int64_t)side.perm[slot] : slot;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int c = co0 + q * 16 + e;
                 D[r * XS_STRIDE + q * 16 + e] =
-                    (row < n_centres && c < c_out) ? load_f<T>(dense, (size_t)row * c_out + c) : 0.f;
+                    (slot < n_centres && c < c_out) ? load_f<T>(dense, (size_t)row * c_out + c) : 0.f;
             }
         }
         __syncthreads();

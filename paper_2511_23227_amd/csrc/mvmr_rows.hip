@@ -206,7 +206,7 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
                     ivc = gather[p < last_triplet ? p : last_triplet];
                 }
                 // byte offset of triplet g0 + lane's source row, out of range past the end of the run
-                const uint32_t offv = g0 + lane < n ? (uint32_t)ivc * ROWB : OOB_OFFSET;
+                const uint32_t offv = g0 + lane < n ? ((uint32_t)ivc & GATHER_INDEX) * ROWB : OOB_OFFSET;
                 // bits of this centre's run inside the group: triplets [lo, hi) of the 64
                 int lo = rel - (int)g0, hi = lo + (int)cn_c;
                 lo = lo < 0 ? 0 : (lo > 64 ? 64 : lo);
@@ -361,8 +361,9 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
             float v = acc[b][j];
 #pragma unroll
             for (int wv = 0; wv < NW - 1; ++wv) v += red[((size_t)wv * NB * 16 + b * 16 + j) * 64 + lane];
-            const int64_t row = row0 + 8 * (j / 4) + 4 * h + (j % 4);
-            if (row < n_centres) {
+            const int64_t slot = row0 + 8 * (j / 4) + 4 * h + (j % 4);
+            if (slot < n_centres) {
+                const int64_t row = side.perm ? (int64_t)side.perm[slot] : slot;
                 if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + b * 32 + c] = v;
                 else dst[(size_t)row * C_DST + b * 32 + c] = (uint16_t)(cvt_pk_bf16(v, 0.f) & 0xffffu);
             }

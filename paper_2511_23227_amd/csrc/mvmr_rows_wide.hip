@@ -180,7 +180,7 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void rows_wide_kernel(const void *
         auto row_offsets = [&](uint32_t first, uint32_t left) -> uint32_t {
             const uint32_t p = first + lane;
             const int32_t iv = gather[p < last_triplet ? p : last_triplet];
-            return (uint32_t)lane < left ? (uint32_t)iv * ROWB : OOB_OFFSET;
+            return (uint32_t)lane < left ? ((uint32_t)iv & GATHER_INDEX) * ROWB : OOB_OFFSET;
         };
         // triplets [lo, lo + len) of a run as a bit mask over the 64 triplets starting at g0
         auto run_window = [&](int rel, uint32_t len, uint32_t g0) -> unsigned long long {
@@ -334,8 +334,9 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void rows_wide_kernel(const void *
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int64_t row = row0 + 32 * sb + 16 * hf + 4 * g + j;
-                    if (row < n_centres) {
+                    const int64_t slot = row0 + 32 * sb + 16 * hf + 4 * g + j;
+                    if (slot < n_centres) {
+                        const int64_t row = side.perm ? (int64_t)side.perm[slot] : slot;
                         const float v = acc[sb][hf][db][j];
                         if constexpr (sizeof(TOut) == 4) dst[(size_t)row * C_DST + db * 16 + n] = v;
                         else dst[(size_t)row * C_DST + db * 16 + n] = (uint16_t)(cvt_pk_bf16(v, 0.f) & 0xffffu);
@@ -353,14 +354,12 @@ int launch_wide(const MvmrArgs &a, hipStream_t stream)
     const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * 2);
     if (a.out_dtype == PCPP_F32) {
         auto kern = rows_wide_kernel<C_SRC, C_DST, float>;
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (int rc = raise_lds_limit(reinterpret_cast<const void *>(kern), lds)) return rc;
         kern<<<(unsigned)grid, WIDE_WAVES * 64, lds, stream>>>(a.feat, a.w, static_cast<float *>(a.dst), a.n_centres,
                                                                a.K, a.gather, last, feat_bytes, a.side, n_blocks);
     } else {
         auto kern = rows_wide_kernel<C_SRC, C_DST, uint16_t>;
-        PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (int rc = raise_lds_limit(reinterpret_cast<const void *>(kern), lds)) return rc;
         kern<<<(unsigned)grid, WIDE_WAVES * 64, lds, stream>>>(a.feat, a.w, static_cast<uint16_t *>(a.dst),
                                                                a.n_centres, a.K, a.gather, last, feat_bytes, a.side,
                                                                n_blocks);

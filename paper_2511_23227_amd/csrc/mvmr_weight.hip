@@ -606,8 +606,7 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     if (n_chunks > 0) {
         // (16-byte row reads: the entry point has checked that x and dy are 16-byte aligned, and rows are 512 bytes)
         if constexpr (BF16 && C_IN == 256 && C_OUT == 256) {
-            PCPP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&weight_lds_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * LDS_BATCH_BYTES));
+            if (int rc = raise_lds_limit(reinterpret_cast<const void *>(&weight_lds_kernel), 2 * LDS_BATCH_BYTES)) return rc;
             weight_lds_kernel<<<(unsigned)n_chunks, LDS_WAVES * 64, 2 * LDS_BATCH_BYTES, stream>>>(
                 static_cast<const uint16_t *>(a.feat), static_cast<const uint16_t *>(a.dense), part, tri_o, a.gather, seg,
                 a.K, a.n_triplets, chunk, n_chunks);

@@ -3,6 +3,9 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+#include <vector>
+
 #include "pcpp_internal.h"
 
 namespace pcpp {
@@ -17,14 +20,34 @@ void set_error(const char *fmt, ...)
     va_end(ap);
 }
 
-namespace {
+// Kernels that need more dynamic LDS than the default limit have the limit raised once per device; the table only
+// remembers what has already been asked for, so that the attribute call is not repeated on every launch.
+int raise_lds_limit(const void *kernel, size_t bytes)
+{
+    struct Entry { const void *kernel; int device; size_t bytes; };
+    static std::mutex mu;
+    static std::vector<Entry> done;
+    int dev = 0;
+    PCPP_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    for (Entry &e : done)
+        if (e.kernel == kernel && e.device == dev) {
+            if (e.bytes >= bytes) return PCPP_OK;
+            PCPP_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+            e.bytes = bytes;
+            return PCPP_OK;
+        }
+    PCPP_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    done.push_back(Entry{kernel, dev, bytes});
+    return PCPP_OK;
+}
 
-size_t elem_size(int dtype) { return dtype == PCPP_F32 ? 4 : 2; }
+namespace {
 
 int check_common(const char *fn, const void *a, const void *b, const void *c, int in_dtype, int out_dtype,
                  int64_t n_in, int64_t n_out, int c_in, int c_out, int K, const int32_t *tri_o,
                  const int32_t *tri_i, const int32_t *tri_k, const int64_t *seg_offsets, int64_t n_triplets,
-                 const void *plan)
+                 const void *plan, size_t plan_bytes, int plan_flags, int need_flags)
 {
     if (n_in < 0 || n_out < 0 || n_triplets < 0 || K < 1) {
         set_error("%s: negative size or K < 1", fn);
@@ -63,24 +86,33 @@ int check_common(const char *fn, const void *a, const void *b, const void *c, in
         set_error("%s: sizes must be below 2^31", fn);
         return PCPP_ERR_UNSUPPORTED;
     }
+    if ((plan_flags & ~PLAN_FLAG_MASK) || (plan_flags & need_flags) != need_flags) {
+        set_error("%s: plan_flags 0x%x lack the part this call reads (0x%x) or hold unknown bits", fn, plan_flags,
+                  need_flags);
+        return PCPP_ERR_INVALID_ARG;
+    }
+    int t = 1;
+    while (t * t * t < K) ++t;
+    if (t * t * t != K) {
+        set_error("%s: K must be a cube", fn);
+        return PCPP_ERR_INVALID_ARG;
+    }
+    const size_t need = plan_layout(n_in, n_out, K, n_triplets, plan_flags).bytes;
+    if (plan_bytes < need) {
+        set_error("%s: plan buffer has %zu bytes, these sizes and flags need %zu", fn, plan_bytes, need);
+        return PCPP_ERR_WORKSPACE;
+    }
     return PCPP_OK;
 }
 
-// t from K = t^3 (the plan layout is keyed on it)
-int cube_root(int K)
-{
-    for (int t = 1; t <= PCPP_MAX_T; ++t)
-        if (t * t * t == K) return t;
-    return -1;
-}
-
-PlanSideView side_view(const void *plan, const SideLayout &s)
+PlanSideView side_view(const void *plan, const SideLayout &s, bool spatial)
 {
     const char *pb = static_cast<const char *>(plan);
     PlanSideView v;
     v.tile_ptr = reinterpret_cast<const uint32_t *>(pb + s.tile_ptr_off);
     v.run_start = reinterpret_cast<const uint32_t *>(pb + s.run_start_off);
-    v.gather = reinterpret_cast<const int32_t *>(pb + s.gather_off);
+    v.gather = s.gather_index >= 0 ? reinterpret_cast<const int32_t *>(pb + s.gather_off) : nullptr;
+    v.perm = spatial ? reinterpret_cast<const int32_t *>(pb + s.perm_off) : nullptr;
     v.n_tiles = s.n_tiles;
     return v;
 }
@@ -115,22 +147,21 @@ size_t pcpp_mvmr_workspace_bytes(int op, int64_t n_in, int64_t n_out, int64_t n_
 int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out_dtype, int64_t n_in,
                   int64_t n_out, int c_in, int c_out, int K, const int32_t *tri_o, const int32_t *tri_i,
                   const int32_t *tri_k, const int64_t *seg_offsets, int64_t n_triplets, const void *plan,
-                  void *workspace, size_t workspace_bytes, void *stream_)
+                  size_t plan_bytes, int plan_flags, void *workspace, size_t workspace_bytes, void *stream_)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     int rc = check_common("pcpp_mvmr_fwd", x, w, out, in_dtype, out_dtype, n_in, n_out, c_in, c_out, K, tri_o, tri_i,
-                          tri_k, seg_offsets, n_triplets, plan);
+                          tri_k, seg_offsets, n_triplets, plan, plan_bytes, plan_flags, PCPP_PLAN_FWD);
     if (rc != PCPP_OK) return rc;
-    const int t = cube_root(K);
-    if (t < 0) { set_error("pcpp_mvmr_fwd: K must be a cube"); return PCPP_ERR_INVALID_ARG; }
     if (n_out == 0) return PCPP_OK;
-    // the forward side of the plan is laid out first whenever it is present, whatever else was requested
-    const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, PCPP_PLAN_FWD);
+    const bool spatial = (plan_flags & PCPP_PLAN_SPATIAL) != 0;
+    const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, plan_flags);
     MvmrArgs a{};
     a.feat = x; a.w = w; a.dst = out; a.dense = nullptr;
     a.in_dtype = in_dtype; a.out_dtype = out_dtype;
     a.n_src = n_in; a.n_centres = n_out; a.c_src = c_in; a.c_dst = c_out; a.K = K;
-    a.gather = tri_i; a.side = side_view(plan, pl.fwd); a.n_triplets = n_triplets;
+    a.side = side_view(plan, pl.fwd, spatial); a.gather = a.side.gather ? a.side.gather : tri_i;
+    a.n_triplets = n_triplets;
     if (mvmr_rows_sel_supported(a)) {
         const size_t need = pcpp_mvmr_workspace_bytes(0, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
         if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
@@ -147,26 +178,26 @@ int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out
 int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, int out_dtype, int64_t n_in,
                         int64_t n_out, int c_in, int c_out, int K, const int32_t *tri_o, const int32_t *tri_i,
                         const int32_t *tri_k, const int64_t *seg_offsets, int64_t n_triplets, const void *plan,
-                        void *workspace, size_t workspace_bytes, void *stream_)
+                        size_t plan_bytes, int plan_flags, void *workspace, size_t workspace_bytes, void *stream_)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     int rc = check_common("pcpp_mvmr_bwd_input", dy, w, dx, in_dtype, out_dtype, n_in, n_out, c_in, c_out, K, tri_o,
-                          tri_i, tri_k, seg_offsets, n_triplets, plan);
+                          tri_i, tri_k, seg_offsets, n_triplets, plan, plan_bytes, plan_flags,
+                          PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT);
     if (rc != PCPP_OK) return rc;
-    const int t = cube_root(K);
-    if (t < 0) { set_error("pcpp_mvmr_bwd_input: K must be a cube"); return PCPP_ERR_INVALID_ARG; }
     const size_t need = pcpp_mvmr_workspace_bytes(1, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
         set_error("pcpp_mvmr_bwd_input: workspace missing, misaligned or smaller than %zu bytes", need);
         return PCPP_ERR_WORKSPACE;
     }
     if (n_in == 0) return PCPP_OK;
-    const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT);
+    const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, plan_flags);
     MvmrArgs a{};
     a.feat = dy; a.w = workspace; a.dst = dx; a.dense = nullptr;
     a.in_dtype = in_dtype; a.out_dtype = out_dtype;
     a.n_src = n_out; a.n_centres = n_in; a.c_src = c_out; a.c_dst = c_in; a.K = K;
-    a.side = side_view(plan, pl.bwd); a.gather = a.side.gather; a.n_triplets = n_triplets;
+    a.side = side_view(plan, pl.bwd, (plan_flags & PCPP_PLAN_SPATIAL) != 0); a.gather = a.side.gather;
+    a.n_triplets = n_triplets;
     // W[k] is [c_out][c_in]; the rows kernel wants (dst = c_in, src = c_out) = W[k]^T
     if (mvmr_rows_sel_supported(a)) {
         if ((rc = mvmr_rows_sel_pack_w(w, workspace, K, c_out, c_in, 1, c_in, in_dtype, stream)) != PCPP_OK) return rc;
@@ -179,28 +210,29 @@ int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, i
 int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype, int64_t n_in, int64_t n_out,
                          int c_in, int c_out, int K, const int32_t *tri_o, const int32_t *tri_i,
                          const int32_t *tri_k, const int64_t *seg_offsets, int64_t n_triplets, const void *plan,
-                         void *workspace, size_t workspace_bytes, void *stream_)
+                         size_t plan_bytes, int plan_flags, void *workspace, size_t workspace_bytes, void *stream_)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     int rc = check_common("pcpp_mvmr_bwd_weight", x, dw, dy, in_dtype, PCPP_F32, n_in, n_out, c_in, c_out, K, tri_o,
-                          tri_i, tri_k, seg_offsets, n_triplets, plan);
+                          tri_i, tri_k, seg_offsets, n_triplets, plan, plan_bytes, plan_flags, PCPP_PLAN_FWD);
     if (rc != PCPP_OK) return rc;
-    const int t = cube_root(K);
-    if (t < 0) { set_error("pcpp_mvmr_bwd_weight: K must be a cube"); return PCPP_ERR_INVALID_ARG; }
     const size_t need = pcpp_mvmr_workspace_bytes(2, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
         set_error("pcpp_mvmr_bwd_weight: workspace missing, misaligned or smaller than %zu bytes", need);
         return PCPP_ERR_WORKSPACE;
     }
-    const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, PCPP_PLAN_FWD);
+    const PlanLayout pl = plan_layout(n_in, n_out, K, n_triplets, plan_flags);
     MvmrArgs a{};
     a.feat = x; a.w = nullptr; a.dst = nullptr; a.dense = dy;
     a.in_dtype = in_dtype; a.out_dtype = PCPP_F32;
     a.n_src = n_in; a.n_centres = n_out; a.c_src = c_in; a.c_dst = c_out; a.K = K;
-    a.gather = tri_i; a.side = side_view(plan, pl.fwd); a.n_triplets = n_triplets;
+    a.side = side_view(plan, pl.fwd, (plan_flags & PCPP_PLAN_SPATIAL) != 0); a.gather = a.side.gather ? a.side.gather : tri_i;
+    a.n_triplets = n_triplets;
     bool handled = false;
     if (n_triplets == 0) return fill_u32(reinterpret_cast<uint32_t *>(dw), 0u, (int64_t)K * c_out * c_in, stream);
-    rc = mvmr_weight_mfma(a, dw, tri_o, seg_offsets, workspace, workspace_bytes, stream, &handled);
+    MvmrArgs am = a;
+    am.gather = tri_i;                               // the matrix-core kernels walk the public (k, o, i) list
+    rc = mvmr_weight_mfma(am, dw, tri_o, seg_offsets, workspace, workspace_bytes, stream, &handled);
     if (rc != PCPP_OK || handled) return rc;
     return mvmr_weight_generic(a, dw, workspace, workspace_bytes, stream);
 }

@@ -30,37 +30,64 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // One side of a plan: triplets grouped around `n_centres` centres (outputs for the forward /
-// weight-gradient side, inputs for the input-gradient side).
-//   tile_ptr  uint32 [K * n_tiles + 1]  start of the (cell k, tile) run in the side's triplet
-//                                       order, k-major; last entry = |T|
-//   run_start uint32 [n_tiles][K][TILE] start of the (cell k, centre tile*TILE + a) run; it ends where
-//                                       the next centre's run starts (for a = TILE-1: at the end of
-//                                       the (k, tile) run)
-//   gather    int32  [|T|]              (input-gradient side only) output index of each triplet in
-//                                       (k, i, o) order; the forward side gathers through tri_i
+// weight-gradient side, inputs for the input-gradient side).  A centre's position in the side's order is its
+// slot; slots are the centre indices themselves, or, in a plan built with PCPP_PLAN_SPATIAL, positions along a
+// space-filling curve (perm[slot] = centre index).
+//   perm      int32  [n_centres]           (spatial plans only) centre index of each slot
+//   tile_ptr  uint32 [K * n_tiles + 1]     start of the (cell k, tile) run in the side's triplet
+//                                          order, k-major; last entry = |T|
+//   run_start uint32 [n_tiles][K][TILE]    start of the (cell k, slot tile*TILE + a) run; it ends where
+//                                          the next slot's run starts (for a = TILE-1: at the end of
+//                                          the (k, tile) run)
+//   gather    int32  [|T|]                 source row of each triplet in (k, slot, source) order, bit 31 set on
+//                                          the last triplet of a (k, slot) run.  The input-gradient side always has
+//                                          one; the forward side has one in spatial plans and otherwise gathers
+//                                          through tri_i.  These arrays follow everything else, one after the
+//                                          other, each align_up(|T| * 4) bytes: `gather_index` counts them.
 struct SideLayout {
     int64_t n_centres = 0;
     int64_t n_tiles = 0;
+    size_t perm_off = 0;
     size_t tile_ptr_off = 0;
     size_t run_start_off = 0;
-    size_t gather_off = 0;
-    size_t end = 0;
+    int gather_index = -1;       // position among the |T|-sized arrays, -1: none
+    size_t gather_off = 0;       // = tail_off + gather_index * align_up(n_triplets * 4)
 };
 
 struct PlanLayout {
     SideLayout fwd;   // valid if flags & PCPP_PLAN_FWD
     SideLayout bwd;   // valid if flags & PCPP_PLAN_BWD_INPUT
+    size_t tail_off = 0;    // start of the |T|-sized arrays
+    int n_tail = 0;         // how many there are
     size_t bytes = 0;
 };
+
+constexpr int PLAN_FLAG_MASK = PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT | PCPP_PLAN_SPATIAL;
+constexpr uint32_t GATHER_LAST = 0x80000000u;     // flag on the last triplet of a run in a plan's gather array
+constexpr uint32_t GATHER_INDEX = 0x7fffffffu;
 
 PlanLayout plan_layout(int64_t n_in, int64_t n_out, int K, int64_t n_triplets, int flags);
 
 struct PlanSideView {
     const uint32_t *tile_ptr;
     const uint32_t *run_start;
-    const int32_t *gather;
+    const int32_t *gather;     // NULL when the side gathers through tri_i
+    const int32_t *perm;       // NULL when slots are centre indices
     int64_t n_tiles;
 };
+
+// Raise a kernel's dynamic LDS limit to `bytes` (once per kernel and device; later calls with no more are free).
+int raise_lds_limit(const void *kernel, size_t bytes);
+
+// ---- spatial order of a point set (spatial_order.hip) ----------------------------------------
+// perm[slot] = index of the point at that position along a Morton curve of cells of pitch `pitch`.
+// scratch: spatial_order_scratch_bytes(n) bytes, 256-byte aligned; scan_status: SPATIAL_ORDER_SCANS consecutive
+// regions of scan_scratch_bytes(spatial_order_scan_items(n)) bytes, all zero when the call starts.
+constexpr int SPATIAL_ORDER_SCANS = 3;
+size_t spatial_order_scratch_bytes(int64_t n);
+int64_t spatial_order_scan_items(int64_t n);
+int spatial_order(const float *xyz, int64_t n, double pitch, int32_t *perm, void *scratch, void *scan_status,
+                  size_t scan_stride, uint32_t *err, hipStream_t stream);
 
 // ---- device-wide exclusive scan of uint32 (scan.hip) ------------------------------------------
 // out[i] = sum_{j<i} in[j] for i in [0, n]; out has n+1 entries (out may alias in when it has
@@ -68,8 +95,10 @@ struct PlanSideView {
 // leaves them non-zero: zero them again before the next scan, or give every scan its own).
 // total64 (device, optional) receives the 64-bit total.
 size_t scan_scratch_bytes(int64_t n);
+// err (device, optional): set to 1 if a wait inside the scan ran out (the results are then undefined);
+// when it is already set the last block stores ~0 as the total.
 int scan_exclusive_u32(const uint32_t *in, uint32_t *out, int64_t n, void *scratch,
-                       unsigned long long *total64, hipStream_t stream);
+                       unsigned long long *total64, uint32_t *err, hipStream_t stream);
 int fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t stream);
 int fill_u64(unsigned long long *p, unsigned long long v, int64_t n, hipStream_t stream);
 

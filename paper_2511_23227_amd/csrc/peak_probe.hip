@@ -37,7 +37,7 @@ extern "C" {
 
 // Launches `blocks` blocks of four waves, each wave issuing iters * 16 MFMAs; returns the number of floating-point
 // operations launched (2 * 16 * 16 * 32 per MFMA), or a negative HIP error code.  sink: at least 256 floats (device).
-double pcpp_probe_mfma_bf16(int blocks, int iters, float *sink, void *stream)
+__attribute__((visibility("default"))) double pcpp_probe_mfma_bf16(int blocks, int iters, float *sink, void *stream)
 {
     if (blocks < 1 || iters < 1 || !sink) return -1.0;
     mfma_issue_loop<<<(unsigned)blocks, 256, 0, static_cast<hipStream_t>(stream)>>>(iters, sink);

@@ -16,7 +16,6 @@ constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_ITEMS;
 constexpr unsigned long long STATUS_SUM = 1ull << 62;        // value = sum of the block's own items
 constexpr unsigned long long STATUS_PREFIX = 2ull << 62;     // value = sum of all items up to the block's last
 constexpr unsigned long long STATUS_VALUE = (1ull << 62) - 1;
-constexpr unsigned long long SCAN_POISON = 1ull << 60;       // added to the prefix when a wait ran out
 constexpr int SCAN_SPIN_LIMIT = 1 << 20;
 
 __device__ inline unsigned long long wave_incl_scan_u64(unsigned long long v, int lane)
@@ -58,7 +57,8 @@ __device__ inline unsigned long long block_incl_scan_u64(unsigned long long v, u
 // written and read with single agent-scope accesses, so no ordering between two words is relied on.
 __global__ __launch_bounds__(SCAN_THREADS) void scan_chained(const uint32_t *in, uint32_t *out,
                                                              int64_t n, unsigned long long *__restrict__ status,
-                                                             int64_t n_blocks, unsigned long long *__restrict__ total64)
+                                                             int64_t n_blocks, unsigned long long *__restrict__ total64,
+                                                             uint32_t *__restrict__ err)
 {
     __shared__ unsigned long long shared_word[2];       // ticket, then the block's exclusive prefix
     const int lane = threadIdx.x & 63;
@@ -94,9 +94,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chained(const uint32_t *in,
                     take = known ? (lowest | (lowest - 1)) : ~0ull;
                     found = known != 0;
                     if (!(empty & take)) break;
-                    if (spin >= SCAN_SPIN_LIMIT) {      // cannot happen on a working device: mark the result
-                        if (empty >> lane & 1) w = 0;
-                        excl += lane == 0 ? SCAN_POISON : 0;
+                    if (spin >= SCAN_SPIN_LIMIT) {      // cannot happen on a working device: raise the error word
+                        if (empty >> lane & 1) w = 0;   // (every later kernel of the build and the host look at it)
+                        if (err && lane == 0) {
+                            __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __threadfence();
+                        }
                         found = true;
                         break;
                     }
@@ -127,7 +130,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chained(const uint32_t *in,
     }
     if (bid == n_blocks - 1 && threadIdx.x == 0) {
         out[n] = (uint32_t)(before + tot);
-        if (total64) *total64 = before + tot;
+        // every earlier block has published by now, and a block raises the error word before it publishes
+        const bool bad = err && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+        if (total64) *total64 = bad ? ~0ull : before + tot;
     }
 }
 
@@ -153,7 +158,7 @@ size_t scan_scratch_bytes(int64_t n)
 }
 
 int scan_exclusive_u32(const uint32_t *in, uint32_t *out, int64_t n, void *scratch,
-                       unsigned long long *total64, hipStream_t stream)
+                       unsigned long long *total64, uint32_t *err, hipStream_t stream)
 {
     auto *status = static_cast<unsigned long long *>(scratch);
     if (n <= 0) {
@@ -164,7 +169,7 @@ int scan_exclusive_u32(const uint32_t *in, uint32_t *out, int64_t n, void *scrat
         return PCPP_OK;
     }
     const int64_t n_blocks = ceil_div(n, SCAN_BLOCK);
-    scan_chained<<<(unsigned)n_blocks, SCAN_THREADS, 0, stream>>>(in, out, n, status, n_blocks, total64);
+    scan_chained<<<(unsigned)n_blocks, SCAN_THREADS, 0, stream>>>(in, out, n, status, n_blocks, total64, err);
     PCPP_HIP_CHECK(hipGetLastError());
     return PCPP_OK;
 }

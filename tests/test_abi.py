@@ -17,6 +17,13 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
     assert set(binding.EXPORTS) <= declared
     assert L.pcpp_version() >= 100
+    # and nothing else: every dynamic symbol the library defines is declared in the header (the toolchain's own
+    # per-file identifiers aside)
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True)
+    exported = {line.split()[-1] for line in out.stdout.splitlines() if line.strip()}
+    exported = {s for s in exported if not s.startswith("__hip_")}
+    assert exported == declared, exported ^ declared
 
 
 def test_size_queries_and_argument_errors_without_gpu():
@@ -34,5 +41,17 @@ def test_size_queries_and_argument_errors_without_gpu():
     rc = L.pcpp_build_triplets(None, 5, None, 5, 0.1, 3, None, None, None, 0, None, ctypes.byref(n), None, 0, 0,
                                None, 0, None)
     assert rc == -1 and b"null" in L.pcpp_last_error()
-    rc = L.pcpp_mvmr_fwd(None, None, None, 0, 0, 1, 1, 4, 4, 27, None, None, None, None, 0, None, None, 0, None)
+    rc = L.pcpp_mvmr_fwd(None, None, None, 0, 0, 1, 1, 4, 4, 27, None, None, None, None, 0, None, 0, 1, None, 0, None)
     assert rc == -1
+    # a plan without the part a call reads, or smaller than these sizes need, is refused before anything is launched
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    args = (p, p, p, 0, 0, 100, 100, 4, 4, 27, p, p, p, p, 10)
+    assert L.pcpp_mvmr_bwd_input(*args, p, 1 << 30, binding.PLAN_FWD, p, 1 << 20, None) == -1
+    assert b"plan_flags" in L.pcpp_last_error()
+    assert L.pcpp_mvmr_fwd(*args, p, 1024, binding.PLAN_FWD, p, 1 << 20, None) == -3
+    # spatial plans are larger (a permutation per side and a private gather array for the forward side)
+    c = L.pcpp_plan_bytes(1000, 500, 3, 20000, 7)
+    assert c >= b + 4 * (1000 + 500 + 20000)
+    assert L.pcpp_build_triplets(p, 5, p, 5, 0.1, 3, None, None, None, 0, None, ctypes.byref(n), None, 0, 0x1000,
+                                 p, 1 << 20, None) == -1

@@ -86,6 +86,9 @@ def test_scene_full(pcpp, sid):
     dict(n_in=2100, n_out=700, r=0.15, t=3, cin=64, cout=128, dt="bf16"),
     dict(n_in=999, n_out=999, r=0.2, t=5, cin=32, cout=32, dt="bf16"),
     dict(n_in=800, n_out=31, r=0.2, t=2, cin=64, cout=64, dt="f32"),
+    # the largest kernel the library accepts: K = 216 (the search tables need more LDS than the default limit)
+    dict(n_in=1100, n_out=900, r=0.22, t=6, cin=12, cout=20, dt="f32"),
+    dict(n_in=1000, n_out=1000, r=0.2, t=6, cin=64, cout=64, dt="bf16"),
     # wide layers (W shared through LDS), K = 125 and K = 27, ragged point counts
     dict(n_in=1500, n_out=1300, r=0.15, t=5, cin=256, cout=256, dt="bf16"),
     dict(n_in=700, n_out=900, r=0.2, t=3, cin=128, cout=128, dt="bf16"),
@@ -155,14 +158,35 @@ def test_dense_cluster_uses_rescan_path(pcpp):
     rng = np.random.default_rng(4)
     p = rng.normal(0.5, 0.02, (1500, 3)).astype(np.float32)
     o, i, k, seg = oracle.build_triplets(p, p, np.float32(0.05), 3)
-    L = pcpp.library()
-    assert L.pcpp_debug_set_list_cap(40) == 0
-    try:
-        T = build_gpu(pcpp, p, p, 0.05, 3, same=True)
-    finally:
-        assert L.pcpp_debug_set_list_cap(512) == 0
+    d = dev(p)
+    flags = pcpp.PLAN_FWD | pcpp.PLAN_BWD_INPUT | pcpp.BUILD_TEST_SHORT_LISTS
+    nbytes = pcpp.library().pcpp_plan_bytes(len(p), len(p), 3, len(o), pcpp.PLAN_FWD | pcpp.PLAN_BWD_INPUT)
+    zeros = lambda: {"plan": torch.zeros(nbytes, dtype=torch.uint8, device="cuda")}
+    T = pcpp.pcpp_build_triplets(d, d, 0.05, 3, plan_flags=flags, capacity=len(o), buffers=zeros())
     assert np.bincount(o).max() > 40
     check_triplets(T, o, i, k, seg)
+    # the same plan as the ordinary paths write
+    T2 = pcpp.pcpp_build_triplets(d, d, 0.05, 3, capacity=len(o), buffers=zeros())
+    assert torch.equal(T.plan[256:], T2.plan[256:])
+
+
+def test_wide_key_path(pcpp):
+    """Lists of more than 160 neighbours when cell and index do not share a word (as for clouds of 2^24 points):
+    per-cell buckets filled with wave ballots.  Same triplets and same plan as the packed-key path."""
+    rng = np.random.default_rng(5)
+    p = np.concatenate([rng.normal(0.5, 0.02, (900, 3)), rng.uniform(0, 1, (600, 3))]).astype(np.float32)
+    r, t = 0.05, 5
+    o, i, k, seg = oracle.build_triplets(p, p, np.float32(r), t)
+    cnt = np.bincount(o)
+    assert ((cnt > 160) & (cnt <= 512)).any()
+    d = dev(p)
+    flags = pcpp.PLAN_FWD | pcpp.PLAN_BWD_INPUT
+    nbytes = pcpp.library().pcpp_plan_bytes(len(p), len(p), t, len(o), flags)
+    zeros = lambda: {"plan": torch.zeros(nbytes, dtype=torch.uint8, device="cuda")}
+    T = pcpp.pcpp_build_triplets(d, d, r, t, plan_flags=flags | pcpp.BUILD_TEST_WIDE_KEYS, capacity=len(o), buffers=zeros())
+    check_triplets(T, o, i, k, seg)
+    T2 = pcpp.pcpp_build_triplets(d, d, r, t, plan_flags=flags, capacity=len(o), buffers=zeros())
+    assert torch.equal(T.plan[256:], T2.plan[256:])
 
 
 def test_error_paths(pcpp):
