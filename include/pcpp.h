@@ -167,6 +167,23 @@ PCPP_API int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int 
                                   const void *plan, size_t plan_bytes, int plan_flags,
                                   void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * pcpp_mvmr_fwd for callers that cannot provide scratch memory or let the library allocate it: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same arguments
+ * and same results as pcpp_mvmr_fwd without the workspace: the packed weights go to a device array of
+ * pcpp_static_scratch_bytes() bytes (24 MiB) that is part of the loaded library, one copy per GPU, held until
+ * the process ends.  The call allocates nothing and creates nothing.
+ * Limits: K * c_out * c_in * (2 bytes for bf16, 6 for fp32) must fit that array, otherwise UNSUPPORTED is
+ * returned and nothing is launched.  Every call on a GPU uses that GPU's one array, so two calls that overlap
+ * in time on one GPU (different streams or threads) race; calls on one stream are ordered and safe.
+ * ------------------------------------------------------------------------------------------- */
+PCPP_API size_t pcpp_static_scratch_bytes(void);
+PCPP_API int pcpp_mvmr_fwd_static(const void *x, const void *w, void *out, int in_dtype, int out_dtype,
+                                  int64_t n_in, int64_t n_out, int c_in, int c_out, int K,
+                                  const int32_t *tri_o, const int32_t *tri_i, const int32_t *tri_k,
+                                  const int64_t *seg_offsets, int64_t n_triplets,
+                                  const void *plan, size_t plan_bytes, int plan_flags, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

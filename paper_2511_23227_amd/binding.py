@@ -20,7 +20,7 @@ ERR_CAPACITY = -2
 EXPORTS = ("pcpp_last_error", "pcpp_version", "pcpp_build_triplets_workspace_bytes",
            "pcpp_build_triplets_workspace_bytes_for", "pcpp_plan_bytes",
            "pcpp_build_triplets", "pcpp_mvmr_workspace_bytes", "pcpp_mvmr_fwd", "pcpp_mvmr_bwd_input",
-           "pcpp_mvmr_bwd_weight")
+           "pcpp_mvmr_bwd_weight", "pcpp_static_scratch_bytes", "pcpp_mvmr_fwd_static")
 
 
 class PcppError(RuntimeError):
@@ -64,6 +64,10 @@ def library() -> ctypes.CDLL:
     L.pcpp_mvmr_bwd_input.argtypes = [vp, vp, vp, i32, i32] + tail
     L.pcpp_mvmr_bwd_weight.restype = i32
     L.pcpp_mvmr_bwd_weight.argtypes = [vp, vp, vp, i32] + tail
+    L.pcpp_static_scratch_bytes.restype = sz
+    L.pcpp_static_scratch_bytes.argtypes = []
+    L.pcpp_mvmr_fwd_static.restype = i32
+    L.pcpp_mvmr_fwd_static.argtypes = [vp, vp, vp, i32, i32] + head + [vp]
     _lib = L
     return L
 
@@ -225,6 +229,20 @@ def pcpp_mvmr_fwd(x: torch.Tensor, w: torch.Tensor, T: Triplets, out: torch.Tens
     _check(L.pcpp_mvmr_fwd(_ptr(x), _ptr(w), _ptr(out), _dtype_code(x), _dtype_code(out), T.n_in, T.n_out, c_in, c_out,
                            K, _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets), T.n_triplets,
                            *_plan_args(T), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def pcpp_mvmr_fwd_static(x: torch.Tensor, w: torch.Tensor, T: Triplets, out: torch.Tensor,
+                         out_dtype: torch.dtype = torch.float32) -> torch.Tensor:
+    """pcpp_mvmr_fwd without a workspace: the packed weights go to the library's own device array, and the call
+    allocates nothing (`out` must be given)."""
+    L = library()
+    assert x.is_cuda and x.is_contiguous() and w.is_contiguous() and x.dtype == w.dtype
+    K, c_out, c_in = w.shape
+    assert K == T.K and x.shape == (T.n_in, c_in) and out.shape == (T.n_out, c_out)
+    _check(L.pcpp_mvmr_fwd_static(_ptr(x), _ptr(w), _ptr(out), _dtype_code(x), _dtype_code(out), T.n_in, T.n_out, c_in,
+                                  c_out, K, _ptr(T.tri_o), _ptr(T.tri_i), _ptr(T.tri_k), _ptr(T.seg_offsets),
+                                  T.n_triplets, *_plan_args(T), _stream()))
     return out
 
 

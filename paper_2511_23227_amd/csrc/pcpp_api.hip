@@ -117,6 +117,33 @@ PlanSideView side_view(const void *plan, const SideLayout &s, bool spatial)
     return v;
 }
 
+// Device memory that the entry point which allocates nothing uses in place of a caller's workspace (packed
+// weights).  One copy per device, held until the process ends; calls that overlap on one device would race on it.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)24 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mu;
+void *scratch_ptr[MAX_DEVICES];      // the array's address on each device, once asked for
+
+int static_scratch(void **out)
+{
+    int dev = 0;
+    PCPP_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) {
+        set_error("pcpp_mvmr_fwd_static: device index %d out of range", dev);
+        return PCPP_ERR_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        PCPP_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return PCPP_OK;
+}
+
 }  // namespace
 }  // namespace pcpp
 
@@ -235,6 +262,26 @@ int pcpp_mvmr_bwd_weight(const void *x, const void *dy, float *dw, int in_dtype,
     rc = mvmr_weight_mfma(am, dw, tri_o, seg_offsets, workspace, workspace_bytes, stream, &handled);
     if (rc != PCPP_OK || handled) return rc;
     return mvmr_weight_generic(a, dw, workspace, workspace_bytes, stream);
+}
+
+size_t pcpp_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int pcpp_mvmr_fwd_static(const void *x, const void *w, void *out, int in_dtype, int out_dtype, int64_t n_in,
+                         int64_t n_out, int c_in, int c_out, int K, const int32_t *tri_o, const int32_t *tri_i,
+                         const int32_t *tri_k, const int64_t *seg_offsets, int64_t n_triplets, const void *plan,
+                         size_t plan_bytes, int plan_flags, void *stream_)
+{
+    const size_t need = pcpp_mvmr_workspace_bytes(0, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
+    if (need > STATIC_SCRATCH_BYTES) {
+        set_error("pcpp_mvmr_fwd_static: the packed weights need %zu bytes, the library's own scratch holds %zu", need,
+                  STATIC_SCRATCH_BYTES);
+        return PCPP_ERR_UNSUPPORTED;
+    }
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != PCPP_OK) return rc;
+    return pcpp_mvmr_fwd(x, w, out, in_dtype, out_dtype, n_in, n_out, c_in, c_out, K, tri_o, tri_i, tri_k, seg_offsets,
+                         n_triplets, plan, plan_bytes, plan_flags, ws, STATIC_SCRATCH_BYTES, stream_);
 }
 
 }  // extern "C"

@@ -50,6 +50,8 @@ def test_size_queries_and_argument_errors_without_gpu():
     assert L.pcpp_mvmr_bwd_input(*args, p, 1 << 30, binding.PLAN_FWD, p, 1 << 20, None) == -1
     assert b"plan_flags" in L.pcpp_last_error()
     assert L.pcpp_mvmr_fwd(*args, p, 1024, binding.PLAN_FWD, p, 1 << 20, None) == -3
+    assert L.pcpp_mvmr_fwd_static(p, p, p, 0, 0, 100, 100, 1024, 1024, 27, p, p, p, p, 10, p, 1 << 30, 1, None) == -4
+    assert L.pcpp_static_scratch_bytes() == 24 << 20
     # spatial plans are larger (a permutation per side and a private gather array for the forward side)
     c = L.pcpp_plan_bytes(1000, 500, 3, 20000, 7)
     assert c >= b + 4 * (1000 + 500 + 20000)
