@@ -189,11 +189,17 @@ int pcpp_mvmr_fwd(const void *x, const void *w, void *out, int in_dtype, int out
     a.n_src = n_in; a.n_centres = n_out; a.c_src = c_in; a.c_dst = c_out; a.K = K;
     a.side = side_view(plan, pl.fwd, spatial); a.gather = a.side.gather ? a.side.gather : tri_i;
     a.n_triplets = n_triplets;
-    if (mvmr_rows_sel_supported(a)) {
+    const bool pc = mvmr_rows_pc_usable(a);
+    if (pc || mvmr_rows_sel_supported(a)) {
         const size_t need = pcpp_mvmr_workspace_bytes(0, n_in, n_out, n_triplets, c_in, c_out, K, in_dtype);
         if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
             set_error("pcpp_mvmr_fwd: workspace missing, misaligned or smaller than %zu bytes", need);
             return PCPP_ERR_WORKSPACE;
+        }
+        if (pc) {
+            if ((rc = mvmr_rows_pc_pack_w(w, workspace, K, c_in, c_out, c_in, 1, stream)) != PCPP_OK) return rc;
+            a.w = workspace;
+            return mvmr_rows_pc(a, stream);
         }
         if ((rc = mvmr_rows_sel_pack_w(w, workspace, K, c_in, c_out, c_in, 1, in_dtype, stream)) != PCPP_OK) return rc;
         a.w = workspace;
@@ -226,6 +232,10 @@ int pcpp_mvmr_bwd_input(const void *dy, const void *w, void *dx, int in_dtype, i
     a.side = side_view(plan, pl.bwd, (plan_flags & PCPP_PLAN_SPATIAL) != 0); a.gather = a.side.gather;
     a.n_triplets = n_triplets;
     // W[k] is [c_out][c_in]; the rows kernel wants (dst = c_in, src = c_out) = W[k]^T
+    if (mvmr_rows_pc_usable(a)) {
+        if ((rc = mvmr_rows_pc_pack_w(w, workspace, K, c_out, c_in, 1, c_in, stream)) != PCPP_OK) return rc;
+        return mvmr_rows_pc(a, stream);
+    }
     if (mvmr_rows_sel_supported(a)) {
         if ((rc = mvmr_rows_sel_pack_w(w, workspace, K, c_out, c_in, 1, c_in, in_dtype, stream)) != PCPP_OK) return rc;
         return mvmr_rows_sel(a, stream);

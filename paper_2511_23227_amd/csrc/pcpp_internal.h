@@ -123,6 +123,11 @@ bool mvmr_rows_sel_supported(const MvmrArgs &a);
 int mvmr_rows_sel_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s,
                          int dtype, hipStream_t stream);
 int mvmr_rows_sel(const MvmrArgs &a, hipStream_t stream);   // a.w = weights packed by mvmr_rows_sel_pack_w
+// wide layers with producer and consumer waves (mvmr_rows_pc.hip); needs a plan side with its own gather array
+bool mvmr_rows_pc_usable(const MvmrArgs &a);
+int mvmr_rows_pc_pack_w(const void *w, void *packed, int K, int c_src, int c_dst, int stride_d, int stride_s,
+                        hipStream_t stream);
+int mvmr_rows_pc(const MvmrArgs &a, hipStream_t stream);   // a.w = weights packed by mvmr_rows_pc_pack_w
 int transpose_w(const void *w, void *wt, int K, int c_out, int c_in, int dtype, hipStream_t stream);
 int mvmr_weight_generic(const MvmrArgs &a, float *dw, void *workspace, size_t workspace_bytes,
                         hipStream_t stream);

@@ -142,3 +142,33 @@ def test_determinism_spatial_wide(pcpp):
                      T.plan.cpu().numpy()[256:]])
     for a, b in zip(*runs):
         assert np.array_equal(a, b)
+
+
+def test_scene5_spatial_sampled(pcpp):
+    """Scene 5 at full size with the plan the benchmark times (PLAN_SPATIAL): forward and input gradient on sampled
+    rows against the oracle, element by element; the public arrays must equal those of the plain build."""
+    s = scenes.make_scene(5)
+    x, w, dy = scenes.make_features(s)
+    rng = np.random.default_rng(56)
+    xyz = dev(s.in_xyz)
+    T = pcpp.pcpp_build_triplets(xyz, xyz, s.radius, s.t, plan_flags=spatial_flags(pcpp))
+    T0 = pcpp.pcpp_build_triplets(xyz, xyz, s.radius, s.t, plan_flags=pcpp.PLAN_FWD)
+    assert T.n_triplets == T0.n_triplets
+    assert torch.equal(T.tri_o, T0.tri_o) and torch.equal(T.tri_i, T0.tri_i) and torch.equal(T.tri_k, T0.tri_k)
+    del T0
+    n = s.n_in
+    bf = torch.bfloat16
+    dx_, dw_, ddy = dev(x, bf), dev(w, bf), dev(dy, bf)
+    so = np.sort(rng.choice(n, 2048, replace=False))
+    o, i, k, _ = oracle.build_triplets(s.in_xyz, s.out_xyz[so], s.radius, s.t)
+    out = pcpp.pcpp_mvmr_fwd(dx_, dw_, T)
+    ui, inv = np.unique(i, return_inverse=True)
+    ref, scale = oracle_fwd(x[ui], w, o, inv.astype(np.int32), k, len(so))
+    assert_close(out[torch.from_numpy(so).cuda()].cpu().numpy(), ref, scale, TOL["bf16"], "scene5 spatial fwd")
+    del out
+    si = np.sort(rng.choice(n, 2048, replace=False))
+    o2, i2, k2, _ = oracle.build_triplets(s.in_xyz[si], s.out_xyz, s.radius, s.t)
+    gx = pcpp.pcpp_mvmr_bwd_input(ddy, dw_, T)
+    uo, inv = np.unique(o2, return_inverse=True)
+    ref, scale = oracle_bwd_input(dy[uo], w, inv.astype(np.int32), i2, k2, len(si))
+    assert_close(gx[torch.from_numpy(si).cuda()].cpu().numpy(), ref, scale, TOL["bf16"], "scene5 spatial bwd_input")
