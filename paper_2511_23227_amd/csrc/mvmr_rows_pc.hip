@@ -14,7 +14,10 @@
 // The two run one cell apart on two LDS tiles, one barrier per cell: while the matrix cores work on cell j the
 // rows of cell j + 1 are in flight.  A consumer's W slice (64 x C_src of the 16.4 MB at K = 125) comes straight from
 // memory / L2 into registers in fragment order, three 32-channel chunks ahead of its use (a ring of four); nothing
-// but S goes through LDS.  Every destination row is accumulated in registers across all cells and written once by its owner: no
+// but S goes through LDS.  A wave issues at most one instruction every four cycles, so the consumers' inner unit
+// (one group of 16 centres x 32 source channels: four MFMAs, 64 cycles of the matrix pipe) holds little else: a
+// test of the group's bit, the four MFMAs and one LDS read at a fixed offset that fetches the group's A piece of
+// the next chunk; all waiting is one explicit instruction per chunk.  Every destination row is accumulated in registers across all cells and written once by its owner: no
 // atomics, fixed summation order.
 //
 // v_mfma_f32_16x16x32_bf16 (A: lane (M = l%16, g = l/16) holds A[M][8g .. 8g+7]; B: lane (N = l%16, g) holds
@@ -68,6 +71,14 @@ __global__ void pack_w_pc_kernel(const uint16_t *__restrict__ w, uint16_t *__res
 __device__ inline void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// c += a . b on the matrix cores, 16 x 16 x 32 bf16, with the accumulator pinned to the accumulation registers and
+// updated in place: the 128 accumulator registers of a consumer wave then never compete with the operands for
+// ordinary vector registers, whatever the control flow around the call looks like.
+__device__ inline void mfma_16x16x32_acc(v4f &c, const v4u &a, const v4u &b)
+{
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
 template <int NCH, typename TOut>
@@ -133,15 +144,22 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
             return (uint32_t)gather[t < last_triplet ? t : last_triplet];
         };
         v2u xq[PC_SLOTS];
-        // rows of triplets [base, base + 32) of a 64-triplet window whose gather words are gv; n = triplets left from base
+        // rows of triplets [base, base + 32) of a 64-triplet window whose gather words are gv; n = triplets left from
+        // base.  Rows past the end of the list are not requested (whole groups of eight) or read as zeros.
         auto issue_rows = [&](uint32_t gv, int half, uint32_t n) {
             const uint32_t offv = ((uint32_t)(lane & 31) < n && (lane >> 5) == half) ? (gv & GATHER_INDEX) * ROWB : OOB_OFFSET;
 #pragma unroll
             for (int j = 0; j < PC_SLOTS; ++j) {
+                if ((j & 7) == 0 && (uint32_t)j >= n) break;                                       // wave-uniform
                 const uint32_t off = (uint32_t)__builtin_amdgcn_readlane((int)offv, 32 * half + j);   // uniform
                 xq[j] = __builtin_amdgcn_raw_buffer_load_b64(frs, (int)(off + (uint32_t)lane * 8u), 0, 0);
             }
         };
+        // (1, 0) and (0, 1) as pairs of bf16, kept in scalar registers: as immediate operands of the dot instruction
+        // their halves would be at the assembler's discretion
+        uint32_t sel_lo = 0x00003f80u, sel_hi = 0x3f800000u;
+        asm volatile("" : "+s"(sel_lo), "+s"(sel_hi));
+        const v2bf one_lo = __builtin_bit_cast(v2bf, sel_lo), one_hi = __builtin_bit_cast(v2bf, sel_hi);
 
         if (n_act > 0) {
             uint32_t st_c, en_c, st_n, en_n, st_nn, en_nn;
@@ -164,7 +182,7 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
 
                 // ---- sums of this cell's runs -> S[s & 1] ------------------------------------------------
                 char *Sb = Smine + (size_t)(s & 1) * SBUF;
-                uint32_t hm = pvalid ? (uint32_t)(__ballot(en_c != st_c) & 0xffffffffull) : 0u;
+                uint32_t hm = __builtin_amdgcn_readfirstlane(pvalid ? (uint32_t)(__ballot(en_c != st_c) & 0xffffffffull) : 0u);
                 if (lane == 0) hasrun[(s & 1) * 4 + p] = hm;
                 {   // rows of zeros for the centres without a run inside a group of 16 that has one
                     uint32_t z = ~hm & (((hm & 0xffffu) ? 0xffffu : 0u) | ((hm >> 16) ? 0xffff0000u : 0u));
@@ -175,6 +193,7 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                     }
                 }
                 float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+                uint32_t fresh = 1u;                       // no row has gone into the sums since the last run ended
                 uint32_t gv_w = gv_c;                      // gather words of the current 64-triplet window
                 for (uint32_t base = 0; base < n_c; base += PC_SLOTS) {
                     const int half = (int)((base >> 5) & 1u);
@@ -185,20 +204,39 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                     const uint32_t left = n_c - base < PC_SLOTS ? n_c - base : PC_SLOTS;
                     const unsigned long long fl = __ballot((gv_w & GATHER_LAST) != 0u && (lane >> 5) == half &&
                                                            (uint32_t)(lane & 31) < left);
-                    const uint32_t flags = (uint32_t)(fl >> (32 * half));
+                    // (all wave-uniform; said explicitly so that the tests below are scalar branches)
+                    const uint32_t flags = __builtin_amdgcn_readfirstlane((uint32_t)(fl >> (32 * half)));   // bit j: a run ends at row j
+                    const uint32_t single = __builtin_amdgcn_readfirstlane(flags & ((flags << 1) | fresh));  // ... and it began there too
+                    fresh = __builtin_amdgcn_readfirstlane((flags >> (left - 1u)) & 1u);
 #pragma unroll
                     for (int j = 0; j < PC_SLOTS; ++j) {
-                        if ((j & 7) == 0 && (uint32_t)j >= left) break;      // wave-uniform
+                        if ((j & 7) == 0 && (uint32_t)j >= left) break;            // wave-uniform
                         const v2u v = xq[j];
-                        a0 += __uint_as_float(v[0] << 16);
-                        a1 += __uint_as_float(v[0] & 0xffff0000u);
-                        a2 += __uint_as_float(v[1] << 16);
-                        a3 += __uint_as_float(v[1] & 0xffff0000u);
-                        if ((flags >> j) & 1u) {                             // wave-uniform: the run ends here
+                        uint32_t v_lo = v[0], v_hi = v[1];
+                        asm volatile("" : "+v"(v_lo), "+v"(v_hi));   // two separate operands for the dot instructions below
+                        if ((single >> j) & 1u) {                                  // wave-uniform: a run of one row is its own sum
                             const int c = __builtin_ctz(hm);
                             hm &= hm - 1u;
-                            *reinterpret_cast<v2u *>(Sb + (size_t)c * SROW) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
-                            a0 = a1 = a2 = a3 = 0.f;
+                            *reinterpret_cast<v2u *>(Sb + (size_t)c * SROW) = v2u{v_lo, v_hi};
+                        } else {
+                            // fp32 sums: lane <-> channels 4 lane .. 4 lane + 3; one dot product with (1, 0) or (0, 1) per channel
+#ifndef PC_NO_DOT
+                            a0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_lo), one_lo, a0, false);
+                            a1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_lo), one_hi, a1, false);
+                            a2 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_hi), one_lo, a2, false);
+                            a3 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_hi), one_hi, a3, false);
+#else
+                            a0 += __uint_as_float(v_lo << 16);
+                            a1 += __uint_as_float(v_lo & 0xffff0000u);
+                            a2 += __uint_as_float(v_hi << 16);
+                            a3 += __uint_as_float(v_hi & 0xffff0000u);
+#endif
+                            if ((flags >> j) & 1u) {                               // wave-uniform: the run ends here
+                                const int c = __builtin_ctz(hm);
+                                hm &= hm - 1u;
+                                *reinterpret_cast<v2u *>(Sb + (size_t)c * SROW) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
+                                a0 = a1 = a2 = a3 = 0.f;
+                            }
                         }
                     }
                 }
@@ -223,6 +261,9 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     constexpr int NC32 = 2 * NCH;                          // 32-channel chunks of a source row
     constexpr size_t W_CELL = (size_t)PC_CONS * NC32 * 4 * 64;
     static_assert(NC32 % 4 == 0, "the ring of four chunks must close over a cell");
+    // s_waitcnt immediate: [3:0] and [15:14] vector-memory count, [6:4] export count, [11:8] LDS / scalar count.
+    // All LDS reads done, and all vector-memory loads but the twelve newest.
+    constexpr int WAIT_CHUNK = 0x007C;
     const v4u *wq = static_cast<const v4u *>(w_) + (size_t)q * NC32 * 4 * 64 + lane;     // + k * W_CELL
     v4f acc[PC_GROUPS][4];
 #pragma unroll
@@ -249,52 +290,38 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         ag |= (h2 & 0xffffu) ? 16u : 0u; ag |= (h2 >> 16) ? 32u : 0u;
         ag |= (h3 & 0xffffu) ? 64u : 0u; ag |= (h3 >> 16) ? 128u : 0u;
         ag = __builtin_amdgcn_readfirstlane(ag);
-        const int n_ag = __builtin_popcount(ag);
-        // lane i: the i-th active group (for the read-ahead, which runs two pieces ahead of the matrix cores)
-        int glist = 0;
-        {
-            uint32_t v = ag;
-            for (int t = 0; t < (lane & 7); ++t) v &= v - 1u;
-            glist = v ? __builtin_ctz(v) : 0;
-        }
-        const int w_next_cell = act[s + 1 < n_act ? s + 1 : s];
         const v4u *w_this = wq + (size_t)act[s] * W_CELL;
-        const v4u *w_next = wq + (size_t)w_next_cell * W_CELL;
-        // A pieces: a queue two deep, read position (chunk rc, index rg in the list of active groups)
-        int rc = 0, rg = 0;
-        auto read_piece = [&]() -> v4u {
-            v4u r = v4u{0u, 0u, 0u, 0u};
-            if (rc < NC32 && n_ag > 0) {                   // wave-uniform
-                const int g = __builtin_amdgcn_readlane(glist, rg);
-                r = *reinterpret_cast<const v4u *>(Sb + (size_t)g * 16 * SROW + rc * 64);
-                if (++rg == n_ag) { rg = 0; ++rc; }
-            }
-            return r;
-        };
-        v4u q0 = read_piece(), q1 = read_piece();
+        const v4u *w_next = wq + (size_t)act[s + 1 < n_act ? s + 1 : s] * W_CELL;
+        // The work of a cell is a sequence of units (chunk ch, active group g), ch-major, four MFMAs each.  Every
+        // group keeps one A piece in registers; a unit requests the group's piece of the next chunk right after its
+        // MFMAs, so that it has a whole chunk's time to arrive.
+        v4u piece[PC_GROUPS];
+#pragma unroll
+        for (int g = 0; g < PC_GROUPS; ++g)
+            if ((ag >> g) & 1u) piece[g] = *reinterpret_cast<const v4u *>(Sb + (size_t)g * 16 * SROW);
 #pragma unroll
         for (int ch = 0; ch < NC32; ++ch) {
-            // three chunks ahead (the next cell's first chunks after the last ones of this cell)
+            // W three chunks ahead (the next cell's first chunks after the last ones of this cell); then one wait for
+            // everything this chunk reads: its own W pieces (all loads but the twelve newest) and the A pieces
             {
                 const v4u *src = ch + 3 < NC32 ? w_this + (size_t)(ch + 3) * 4 * 64 : w_next + (size_t)(ch + 3 - NC32) * 4 * 64;
 #pragma unroll
                 for (int cg = 0; cg < 4; ++cg) wb[(ch + 3) & 3][cg] = src[cg * 64];
             }
+            __builtin_amdgcn_s_waitcnt(WAIT_CHUNK);
 #pragma unroll
             for (int g = 0; g < PC_GROUPS; ++g) {
                 if (!((ag >> g) & 1u)) continue;           // wave-uniform
-                const v4u a = q0;
-                q0 = q1;
-                q1 = read_piece();
 #pragma unroll
-                for (int cg = 0; cg < 4; ++cg)
-                    acc[g][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a),
-                                                                        __builtin_bit_cast(v8bf, wb[ch & 3][cg]),
-                                                                        acc[g][cg], 0, 0, 0);
+                for (int cg = 0; cg < 4; ++cg) mfma_16x16x32_acc(acc[g][cg], piece[g], wb[ch & 3][cg]);
+                if (ch + 1 < NC32) piece[g] = *reinterpret_cast<const v4u *>(Sb + (size_t)g * 16 * SROW + (ch + 1) * 64);
             }
         }
         lds_barrier();
     }
+    // the matrix cores' last results must have landed before ordinary instructions read the accumulators (the
+    // compiler cannot see inside the MFMA statements, so the wait states are spelled out)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     // every row once, by its owner
     const int64_t slot0 = vb * PC_ROWS;
 #pragma unroll
