@@ -28,6 +28,8 @@
 //       packed piece (((k * NQ + q) * NC32 + c) * 4 + cg) * 64 + lane, element e
 //             = W(k, dst 64 q + 16 cg + lane%16, src 32 c + 8 (lane/16) + e)
 // The gather array of the plan side must carry GATHER_LAST on the last triplet of every (cell, centre) run.
+#include <type_traits>
+
 #include "mvmr_rows_common.h"
 
 namespace pcpp {
@@ -81,6 +83,21 @@ __device__ inline void mfma_16x16x32_acc(v4f &c, const v4u &a, const v4u &b)
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
+// One A piece from LDS.  The read is outside the compiler's bookkeeping of outstanding memory operations, and so
+// are the waits for it (lds_wait): a consumer keeps exactly one read per active group in flight, in the order in
+// which the pieces are used, so "all but the newest two have arrived" is enough whenever three or more groups are
+// active -- a count the compiler cannot know and would replace by a wait for everything.
+template <int OFFSET>
+__device__ inline void lds_read_piece(v4u &dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET));
+}
+template <int N>
+__device__ inline void lds_wait()
+{
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+
 template <int NCH, typename TOut>
 __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
                                                              TOut *__restrict__ dst, int64_t n_centres, int K,
@@ -95,7 +112,10 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char *S = lds;                                                 // [2][PC_ROWS][SROW]
     uint32_t *hasrun = reinterpret_cast<uint32_t *>(lds + 2 * SBUF);   // [2][4]: bit c of word p = centre 32 p + c has a run
-    int *act = reinterpret_cast<int *>(hasrun + 8);                // active cells, act[MAX_K] = their number
+    uint32_t *rank_tab = hasrun + 8;                               // [PC_PROD][32]: a producer's centres with a run, in order
+    int *act = reinterpret_cast<int *>(rank_tab + PC_PROD * 32);   // active cells, act[MAX_K] = their number
+    constexpr uint32_t DUMMY_OFF = 2 * SBUF + (8 + PC_PROD * 32) * 4 + (MAX_K + 1) * 4 + 12;   // [PC_PROD][ROWB]: where rows
+    static_assert(DUMMY_OFF % 16 == 0, "alignment of the scratch rows");                       // past a list's end are stored
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t per_xcd = gridDim.x / NUM_XCD;
     const int64_t vb = (int64_t)(blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
@@ -130,7 +150,6 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         const uint32_t *tends = side.tile_ptr + tl + 1;
         const bool last_in_tile = cl == TILE - 1;
         const __amdgpu_buffer_rsrc_t frs = make_rsrc(feat_, feat_bytes);
-        char *Smine = S + (size_t)(32 * p) * SROW + lane * 8;
 
         // bounds of the runs of cell act[j] (clamped; steps past the end are masked by their callers)
         auto load_bounds = [&](int j, uint32_t &st, uint32_t &en) {
@@ -155,11 +174,6 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                 xq[j] = __builtin_amdgcn_raw_buffer_load_b64(frs, (int)(off + (uint32_t)lane * 8u), 0, 0);
             }
         };
-        // (1, 0) and (0, 1) as pairs of bf16, kept in scalar registers: as immediate operands of the dot instruction
-        // their halves would be at the assembler's discretion
-        uint32_t sel_lo = 0x00003f80u, sel_hi = 0x3f800000u;
-        asm volatile("" : "+s"(sel_lo), "+s"(sel_hi));
-        const v2bf one_lo = __builtin_bit_cast(v2bf, sel_lo), one_hi = __builtin_bit_cast(v2bf, sel_hi);
 
         if (n_act > 0) {
             uint32_t st_c, en_c, st_n, en_n, st_nn, en_nn;
@@ -181,19 +195,30 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                 const uint32_t gv_nn = load_gather(s0_nn);
 
                 // ---- sums of this cell's runs -> S[s & 1] ------------------------------------------------
-                char *Sb = Smine + (size_t)(s & 1) * SBUF;
-                uint32_t hm = __builtin_amdgcn_readfirstlane(pvalid ? (uint32_t)(__ballot(en_c != st_c) & 0xffffffffull) : 0u);
+                // Straight-line code per row (a taken branch costs a wave more than the dozen instructions it would
+                // skip): every row is added to the four fp32 sums of its lane (lane <-> channels 4 lane .. 4 lane + 3;
+                // v_dot2c_f32_bf16 would halve the instructions but runs at a quarter of the rate), the sums so far are
+                // rounded to bf16 and stored to the
+                // S row of the run's centre -- the store of the run's last row is the one that stays -- and the sums are
+                // cleared behind a run's last row.
+                const uint32_t hm = __builtin_amdgcn_readfirstlane(pvalid ? (uint32_t)(__ballot(en_c != st_c) & 0xffffffffull) : 0u);
                 if (lane == 0) hasrun[(s & 1) * 4 + p] = hm;
-                {   // rows of zeros for the centres without a run inside a group of 16 that has one
-                    uint32_t z = ~hm & (((hm & 0xffffu) ? 0xffffu : 0u) | ((hm >> 16) ? 0xffff0000u : 0u));
-                    while (z) {                            // wave-uniform
-                        const int c = __builtin_ctz(z);
-                        z &= z - 1u;
-                        *reinterpret_cast<v2u *>(Sb + (size_t)c * SROW) = v2u{0u, 0u};
+                {   // rows of zeros for the centres without a run inside a group of 16 that has one: lane (c, half)
+                    // clears half a row
+                    const uint32_t z = ~hm & (((hm & 0xffffu) ? 0xffffu : 0u) | ((hm >> 16) ? 0xffff0000u : 0u));
+                    if ((z >> (lane & 31)) & 1u) {
+                        char *zp = S + (size_t)(s & 1) * SBUF + (size_t)(32 * p + (lane & 31)) * SROW + (lane >> 5) * 256;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) *reinterpret_cast<v4u *>(zp + 16 * e) = v4u{0u, 0u, 0u, 0u};
                     }
                 }
+                // the centres with a run, by rank: the run that ends r-th belongs to centre tab[r]
+                uint32_t *tab = rank_tab + p * 32;
+                if (lane < 32 && ((hm >> lane) & 1u)) tab[__popc(hm & ((1u << lane) - 1u))] = (uint32_t)lane;
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
                 float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-                uint32_t fresh = 1u;                       // no row has gone into the sums since the last run ended
+                uint32_t ends_before = 0u;                 // runs that ended in earlier passes
                 uint32_t gv_w = gv_c;                      // gather words of the current 64-triplet window
                 for (uint32_t base = 0; base < n_c; base += PC_SLOTS) {
                     const int half = (int)((base >> 5) & 1u);
@@ -204,40 +229,30 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                     const uint32_t left = n_c - base < PC_SLOTS ? n_c - base : PC_SLOTS;
                     const unsigned long long fl = __ballot((gv_w & GATHER_LAST) != 0u && (lane >> 5) == half &&
                                                            (uint32_t)(lane & 31) < left);
-                    // (all wave-uniform; said explicitly so that the tests below are scalar branches)
                     const uint32_t flags = __builtin_amdgcn_readfirstlane((uint32_t)(fl >> (32 * half)));   // bit j: a run ends at row j
-                    const uint32_t single = __builtin_amdgcn_readfirstlane(flags & ((flags << 1) | fresh));  // ... and it began there too
-                    fresh = __builtin_amdgcn_readfirstlane((flags >> (left - 1u)) & 1u);
+                    // lane j: where row j's sums go (byte offset of its centre's S row in the block's LDS; rows past the
+                    // end of the list, which are zeros, go to a scratch row)
+                    const uint32_t rk = ends_before + (uint32_t)__popc(flags & ((1u << (lane & 31)) - 1u));
+                    const uint32_t ctr = tab[rk < 32u ? rk : 31u] & 31u;
+                    const uint32_t dsto = (uint32_t)(lane & 31) < left ? (uint32_t)(s & 1) * SBUF + (32u * p + ctr) * SROW
+                                                                       : DUMMY_OFF + (uint32_t)p * ROWB;
+                    ends_before += (uint32_t)__popc(flags);
 #pragma unroll
                     for (int j = 0; j < PC_SLOTS; ++j) {
                         if ((j & 7) == 0 && (uint32_t)j >= left) break;            // wave-uniform
                         const v2u v = xq[j];
-                        uint32_t v_lo = v[0], v_hi = v[1];
-                        asm volatile("" : "+v"(v_lo), "+v"(v_hi));   // two separate operands for the dot instructions below
-                        if ((single >> j) & 1u) {                                  // wave-uniform: a run of one row is its own sum
-                            const int c = __builtin_ctz(hm);
-                            hm &= hm - 1u;
-                            *reinterpret_cast<v2u *>(Sb + (size_t)c * SROW) = v2u{v_lo, v_hi};
-                        } else {
-                            // fp32 sums: lane <-> channels 4 lane .. 4 lane + 3; one dot product with (1, 0) or (0, 1) per channel
-#ifndef PC_NO_DOT
-                            a0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_lo), one_lo, a0, false);
-                            a1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_lo), one_hi, a1, false);
-                            a2 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_hi), one_lo, a2, false);
-                            a3 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, v_hi), one_hi, a3, false);
-#else
-                            a0 += __uint_as_float(v_lo << 16);
-                            a1 += __uint_as_float(v_lo & 0xffff0000u);
-                            a2 += __uint_as_float(v_hi << 16);
-                            a3 += __uint_as_float(v_hi & 0xffff0000u);
-#endif
-                            if ((flags >> j) & 1u) {                               // wave-uniform: the run ends here
-                                const int c = __builtin_ctz(hm);
-                                hm &= hm - 1u;
-                                *reinterpret_cast<v2u *>(Sb + (size_t)c * SROW) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
-                                a0 = a1 = a2 = a3 = 0.f;
-                            }
-                        }
+                        a0 += __uint_as_float(v[0] << 16);
+                        a1 += __uint_as_float(v[0] & 0xffff0000u);
+                        a2 += __uint_as_float(v[1] << 16);
+                        a3 += __uint_as_float(v[1] & 0xffff0000u);
+                        const uint32_t off = (uint32_t)__builtin_amdgcn_readlane((int)dsto, j);
+                        *reinterpret_cast<v2u *>(lds + off + lane * 8) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
+                        // all-ones while the run goes on, zero behind its last row (wave-uniform, a scalar)
+                        const uint32_t keep = ((flags >> j) & 1u) - 1u;
+                        a0 = __uint_as_float(__float_as_uint(a0) & keep);
+                        a1 = __uint_as_float(__float_as_uint(a1) & keep);
+                        a2 = __uint_as_float(__float_as_uint(a2) & keep);
+                        a3 = __uint_as_float(__float_as_uint(a3) & keep);
                     }
                 }
                 // ---- rows of the next cell ------------------------------------------------------------
@@ -262,8 +277,8 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     constexpr size_t W_CELL = (size_t)PC_CONS * NC32 * 4 * 64;
     static_assert(NC32 % 4 == 0, "the ring of four chunks must close over a cell");
     // s_waitcnt immediate: [3:0] and [15:14] vector-memory count, [6:4] export count, [11:8] LDS / scalar count.
-    // All LDS reads done, and all vector-memory loads but the twelve newest.
-    constexpr int WAIT_CHUNK = 0x007C;
+    // All vector-memory loads but the twelve newest done.
+    constexpr int WAIT_W = 0x0F7C;
     const v4u *wq = static_cast<const v4u *>(w_) + (size_t)q * NC32 * 4 * 64 + lane;     // + k * W_CELL
     v4f acc[PC_GROUPS][4];
 #pragma unroll
@@ -294,29 +309,47 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         const v4u *w_next = wq + (size_t)act[s + 1 < n_act ? s + 1 : s] * W_CELL;
         // The work of a cell is a sequence of units (chunk ch, active group g), ch-major, four MFMAs each.  Every
         // group keeps one A piece in registers; a unit requests the group's piece of the next chunk right after its
-        // MFMAs, so that it has a whole chunk's time to arrive.
+        // MFMAs, so the piece a unit needs is always the oldest read in flight and n_ag - 1 newer ones follow it.
+        const int n_ag = __builtin_popcount(ag);
+        const uint32_t sb_addr = (uint32_t)(uintptr_t)(Sb - lds);       // the dynamic LDS block starts at address 0 (no static LDS)
         v4u piece[PC_GROUPS];
-#pragma unroll
-        for (int g = 0; g < PC_GROUPS; ++g)
-            if ((ag >> g) & 1u) piece[g] = *reinterpret_cast<const v4u *>(Sb + (size_t)g * 16 * SROW);
-#pragma unroll
-        for (int ch = 0; ch < NC32; ++ch) {
-            // W three chunks ahead (the next cell's first chunks after the last ones of this cell); then one wait for
-            // everything this chunk reads: its own W pieces (all loads but the twelve newest) and the A pieces
+        constexpr int GROW = 16 * (int)SROW;
+#define PCPP_PC_FIRST(g) if ((ag >> g) & 1u) lds_read_piece<g * GROW>(piece[g], sb_addr);
+        PCPP_PC_FIRST(0) PCPP_PC_FIRST(1) PCPP_PC_FIRST(2) PCPP_PC_FIRST(3)
+        PCPP_PC_FIRST(4) PCPP_PC_FIRST(5) PCPP_PC_FIRST(6) PCPP_PC_FIRST(7)
+#undef PCPP_PC_FIRST
+        auto chunk = [&](auto ch_tag) {
+            constexpr int ch = decltype(ch_tag)::value;
+            // W three chunks ahead (the next cell's first chunks after the last ones of this cell), then wait for this
+            // chunk's W pieces: all loads but the twelve newest
             {
-                const v4u *src = ch + 3 < NC32 ? w_this + (size_t)(ch + 3) * 4 * 64 : w_next + (size_t)(ch + 3 - NC32) * 4 * 64;
+                constexpr int pre = (ch + 3) % NC32;       // chunk to request: of this cell, or of the next one
+                const v4u *src = (ch + 3 < NC32 ? w_this : w_next) + (size_t)pre * 4 * 64;
 #pragma unroll
                 for (int cg = 0; cg < 4; ++cg) wb[(ch + 3) & 3][cg] = src[cg * 64];
             }
-            __builtin_amdgcn_s_waitcnt(WAIT_CHUNK);
-#pragma unroll
-            for (int g = 0; g < PC_GROUPS; ++g) {
-                if (!((ag >> g) & 1u)) continue;           // wave-uniform
+            __builtin_amdgcn_s_waitcnt(WAIT_W);
+            if (n_ag < 3) lds_wait<0>();                   // wave-uniform
+            auto unit = [&](auto g_tag) {
+                constexpr int g = decltype(g_tag)::value;
+                uint32_t on = (ag >> g) & 1u;
+                asm volatile("" : "+s"(on));               // a scalar, tested by a scalar branch
+                if (!on) return;
+                lds_wait<2>();
 #pragma unroll
                 for (int cg = 0; cg < 4; ++cg) mfma_16x16x32_acc(acc[g][cg], piece[g], wb[ch & 3][cg]);
-                if (ch + 1 < NC32) piece[g] = *reinterpret_cast<const v4u *>(Sb + (size_t)g * 16 * SROW + (ch + 1) * 64);
-            }
-        }
+                if constexpr (ch + 1 < NC32) lds_read_piece<g * GROW + (ch + 1) * 64>(piece[g], sb_addr);
+            };
+            unit(std::integral_constant<int, 0>{}); unit(std::integral_constant<int, 1>{});
+            unit(std::integral_constant<int, 2>{}); unit(std::integral_constant<int, 3>{});
+            unit(std::integral_constant<int, 4>{}); unit(std::integral_constant<int, 5>{});
+            unit(std::integral_constant<int, 6>{}); unit(std::integral_constant<int, 7>{});
+        };
+        static_assert(NC32 == 8 && PC_GROUPS == 8, "the chunk and unit sequences are written out for eight of each");
+        chunk(std::integral_constant<int, 0>{}); chunk(std::integral_constant<int, 1>{});
+        chunk(std::integral_constant<int, 2>{}); chunk(std::integral_constant<int, 3>{});
+        chunk(std::integral_constant<int, 4>{}); chunk(std::integral_constant<int, 5>{});
+        chunk(std::integral_constant<int, 6>{}); chunk(std::integral_constant<int, 7>{});
         lds_barrier();
     }
     // the matrix cores' last results must have landed before ordinary instructions read the accumulators (the
@@ -365,7 +398,7 @@ int mvmr_rows_pc(const MvmrArgs &a, hipStream_t stream)
     constexpr int NCH = 4;
     const int64_t n_blocks = ceil_div(a.n_centres, PC_ROWS);
     const int64_t grid = ceil_div(n_blocks, NUM_XCD) * NUM_XCD;
-    const size_t lds = (size_t)2 * PC_ROWS * (64 * NCH * 2 + 16) + 8 * sizeof(uint32_t) + (MAX_K + 1) * sizeof(int);
+    const size_t lds = (size_t)2 * PC_ROWS * (64 * NCH * 2 + 16) + (8 + PC_PROD * 32) * sizeof(uint32_t) + (MAX_K + 1) * sizeof(int) + 12 + PC_PROD * 64 * NCH * 2;
     const uint32_t last = (uint32_t)(a.n_triplets - 1);
     const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * a.c_src * 2);
     if (a.out_dtype == PCPP_F32) {
