@@ -20,7 +20,7 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build(force=False) if not os.path.exists(LIB) else LIB
+        path = _build(force=False)
         L = ctypes.CDLL(path)
         i64, i32, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_float
         p = ctypes.c_void_p
@@ -31,6 +31,10 @@ def lib():
             f.restype = None
             f.argtypes = [p, p, p, i64, i64, i32, i32, i32, p, p, p, i64]
         L.oracle_num_threads.restype = i32
+        L.oracle_build_triplets_general.restype = i64
+        L.oracle_build_triplets_general.argtypes = [p, p, p, p, i32, f32, i32, i32, p, p, p, i64, p]
+        L.oracle_voxel_subsample.restype = i64
+        L.oracle_voxel_subsample.argtypes = [p, i64, f32, p]
         _lib = L
     return _lib
 
@@ -115,3 +119,36 @@ def mvmr_bwd_weight(x, dy, tri_o, tri_i, tri_k, K):
     lib().oracle_mvmr_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), x.shape[0], dy.shape[0], c_in, c_out, K,
                                  _ptr(o), _ptr(i), _ptr(k), len(o))
     return dw
+
+
+MODE_BALL, MODE_VOXEL = 0, 1
+
+
+def build_triplets_general(in_xyz, out_xyz, size, t, mode=MODE_BALL, in_offsets=None, out_offsets=None):
+    """Triplets over a batch of clouds (offsets into the concatenated arrays; None = one cloud), in ball mode
+    (size = radius, Sec. 3.2 "Definition") or voxel mode (size = voxel pitch, the degraded operator of Sec. 3.2
+    "Voxel Convolution as a Special Case").  Returns (tri_o, tri_i, tri_k, seg_offsets) in (k, o, i) order."""
+    a, b = _f32xyz(in_xyz), _f32xyz(out_xyz)
+    io = np.ascontiguousarray([0, len(a)] if in_offsets is None else in_offsets, dtype=np.int64)
+    oo = np.ascontiguousarray([0, len(b)] if out_offsets is None else out_offsets, dtype=np.int64)
+    assert len(io) == len(oo) and io[0] == 0 and oo[0] == 0 and io[-1] == len(a) and oo[-1] == len(b)
+    nb = len(io) - 1
+    sz = float(np.float32(size))
+    args = (_ptr(a), _ptr(b), _ptr(io), _ptr(oo), nb, sz, int(t), int(mode))
+    n = int(lib().oracle_build_triplets_general(*args, None, None, None, 0, None))
+    if n < 0:
+        raise ValueError("voxel mode needs an odd t")
+    K = int(t) ** 3
+    o = np.empty(n, np.int32); i = np.empty(n, np.int32); k = np.empty(n, np.int32)
+    seg = np.zeros(K + 1, np.int64)
+    m = int(lib().oracle_build_triplets_general(*args, _ptr(o), _ptr(i), _ptr(k), n, _ptr(seg)))
+    assert m == n
+    return o, i, k, seg
+
+
+def voxel_subsample(xyz, pitch):
+    """Indices (ascending) of the lowest-index point of every occupied voxel of the given pitch (Sec. 4.1)."""
+    a = _f32xyz(xyz)
+    kept = np.empty(len(a), np.int32)
+    m = int(lib().oracle_voxel_subsample(_ptr(a), len(a), float(np.float32(pitch)), _ptr(kept)))
+    return kept[:m].copy()
