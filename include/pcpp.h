@@ -66,6 +66,16 @@ extern "C" {
 #define PCPP_BUILD_TEST_WIDE_KEYS    0x200  /* treat cell and index as too wide to share one 32-bit word, as for
                                                clouds of 2^24 points or more                                  */
 
+#define PCPP_BUILD_VOXEL             0x400  /* accepted in plan_flags by pcpp_build_triplets[_batched]: build the triplets
+                                               of the degraded operator of Sec. 3.2 ("Voxel Convolution as a Special
+                                               Case"; "Ours (degraded)" in Sec. 4.2), i.e. sparse voxel convolution:
+                                               `radius` is then the pitch v of a global voxelisation, t must be odd,
+                                               voxel of a coordinate = floor((double)p / (double)v); input i is a
+                                               neighbour of output o iff their voxels differ by at most h = (t-1)/2
+                                               along every axis, and k = ((dx+h)*t + dy+h)*t + dz+h with (dx, dy, dz) the
+                                               voxel offset input minus output.  Everything else (order of T, plan,
+                                               compute calls) is unchanged. */
+
 #define PCPP_MAX_T  6            /* K = t^3 <= 216 */
 
 /* Message for the last error returned on the calling thread (never NULL). HOST. */
@@ -120,6 +130,44 @@ PCPP_API int pcpp_build_triplets(const float *in_xyz, int64_t n_in,
                                  void *plan, size_t plan_bytes, int plan_flags,
                                  void *workspace, size_t workspace_bytes,
                                  void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Triplet construction over a batch of clouds held as concatenated arrays plus offsets (the jagged batch
+ * representation of Sec. 4.1, implementation details): cloud b owns inputs [in_batch_offsets[b],
+ * in_batch_offsets[b+1]) and outputs [out_batch_offsets[b], out_batch_offsets[b+1]); a triplet pairs points of the same
+ * cloud only, whatever their coordinates.  Both offset arrays are DEVICE int32 [n_batches + 1], ascending, first
+ * entry 0, last entry n_in / n_out; both NULL (with n_batches = 1) is pcpp_build_triplets.  Triplet indices refer to
+ * the concatenated arrays, so the compute calls take the whole batch as one cloud.  1 <= n_batches <= 65536.
+ * Everything else as pcpp_build_triplets.
+ * ------------------------------------------------------------------------------------------- */
+PCPP_API int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in,
+                                         const float *out_xyz, int64_t n_out,
+                                         const int32_t *in_batch_offsets, const int32_t *out_batch_offsets,
+                                         int n_batches,
+                                         float radius, int t,
+                                         int32_t *tri_o, int32_t *tri_i, int32_t *tri_k, int64_t capacity,
+                                         int64_t *seg_offsets,
+                                         int64_t *n_triplets,
+                                         void *plan, size_t plan_bytes, int plan_flags,
+                                         void *workspace, size_t workspace_bytes,
+                                         void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Voxel-grid down-sampling that keeps original coordinates (Sec. 4.1, implementation details): the output points
+ * of a strided layer.  For every occupied voxel of pitch `pitch` (voxel of a coordinate = floor((double)p /
+ * (double)pitch)) the point with the lowest index is kept.
+ *   kept    [n] int32 (room for all points): indices of the kept points, ascending
+ *   n_kept  HOST int64: their number (pinned host memory is written by the device, as in pcpp_build_triplets)
+ *   workspace: pcpp_voxel_subsample_workspace_bytes(n) bytes, 256-byte aligned
+ * The call waits for its result.  A strided layer is then pcpp_build_triplets with out_xyz = the kept points'
+ * coordinates; the up-sampling layer of a decoder is the same call with the roles of the two point sets swapped
+ * (more outputs than inputs is an ordinary case).
+ * Errors: INVALID_ARG, WORKSPACE, UNSUPPORTED (n >= 2^31), HIP.  Coordinates beyond 2^20 voxels from the origin fall
+ * into the outermost voxel.
+ * ------------------------------------------------------------------------------------------- */
+PCPP_API size_t pcpp_voxel_subsample_workspace_bytes(int64_t n);
+PCPP_API int pcpp_voxel_subsample(const float *xyz, int64_t n, float pitch, int32_t *kept, int64_t *n_kept,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * MVMR forward, Eq. (1) of Sec. 3.1.1:  out[o, :] = sum_{(o,i,k) in T} W[k] x[i, :].

@@ -13,14 +13,15 @@ LIB_PATH = os.path.join(HERE, "libpcpp.so")
 
 PCPP_F32, PCPP_BF16 = 0, 1
 PLAN_FWD, PLAN_BWD_INPUT, PLAN_SPATIAL = 1, 2, 4
-BUILD_TEST_SHORT_LISTS, BUILD_TEST_WIDE_KEYS = 0x100, 0x200
+BUILD_TEST_SHORT_LISTS, BUILD_TEST_WIDE_KEYS, BUILD_VOXEL = 0x100, 0x200, 0x400
 PLAN_MASK = PLAN_FWD | PLAN_BWD_INPUT | PLAN_SPATIAL
 ERR_CAPACITY = -2
 
 EXPORTS = ("pcpp_last_error", "pcpp_version", "pcpp_build_triplets_workspace_bytes",
            "pcpp_build_triplets_workspace_bytes_for", "pcpp_plan_bytes",
            "pcpp_build_triplets", "pcpp_mvmr_workspace_bytes", "pcpp_mvmr_fwd", "pcpp_mvmr_bwd_input",
-           "pcpp_mvmr_bwd_weight", "pcpp_static_scratch_bytes", "pcpp_mvmr_fwd_static")
+           "pcpp_mvmr_bwd_weight", "pcpp_static_scratch_bytes", "pcpp_mvmr_fwd_static",
+           "pcpp_build_triplets_batched", "pcpp_voxel_subsample_workspace_bytes", "pcpp_voxel_subsample")
 
 
 class PcppError(RuntimeError):
@@ -54,6 +55,13 @@ def library() -> ctypes.CDLL:
     L.pcpp_build_triplets.restype = i32
     L.pcpp_build_triplets.argtypes = [vp, i64, vp, i64, f32, i32, vp, vp, vp, i64, vp,
                                       ctypes.POINTER(i64), vp, sz, i32, vp, sz, vp]
+    L.pcpp_build_triplets_batched.restype = i32
+    L.pcpp_build_triplets_batched.argtypes = [vp, i64, vp, i64, vp, vp, i32, f32, i32, vp, vp, vp, i64, vp,
+                                              ctypes.POINTER(i64), vp, sz, i32, vp, sz, vp]
+    L.pcpp_voxel_subsample_workspace_bytes.restype = sz
+    L.pcpp_voxel_subsample_workspace_bytes.argtypes = [i64]
+    L.pcpp_voxel_subsample.restype = i32
+    L.pcpp_voxel_subsample.argtypes = [vp, i64, f32, vp, ctypes.POINTER(i64), vp, sz, vp]
     L.pcpp_mvmr_workspace_bytes.restype = sz
     L.pcpp_mvmr_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
     head = [i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, sz, i32]     # sizes, triplets, plan
@@ -141,23 +149,26 @@ def pcpp_count_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
 
 def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: float, t: int,
                         plan_flags: int = PLAN_FWD | PLAN_BWD_INPUT, capacity: int | None = None,
-                        buffers: dict | None = None) -> Triplets:
+                        buffers: dict | None = None, in_offsets: torch.Tensor | None = None,
+                        out_offsets: torch.Tensor | None = None) -> Triplets:
     """Triplet construction (Sec. 3.2 with the fixed-radius search of Sec. 4.1) and reordering by (k, o, i).
 
     in_xyz [n_in,3], out_xyz [n_out,3]: contiguous float32 CUDA tensors.  Without `capacity` room for 48
     triplets per output point is provided; if that is too little the call reports the exact count and is
     repeated once with it (so the search runs once in the common case).  `buffers` may carry preallocated
     'tri_o','tri_i','tri_k','seg_offsets','plan','workspace' tensors to reuse.  plan_flags may include
-    PLAN_SPATIAL (tiles follow a space-filling order; for wide layers) and the BUILD_TEST_* aids.
+    PLAN_SPATIAL (tiles follow a space-filling order; for wide layers), BUILD_VOXEL (the degraded, sparse-voxel
+    operator of Sec. 3.2: `radius` is the voxel pitch) and the BUILD_TEST_* aids.  in_offsets / out_offsets: int32
+    CUDA tensors [n_batches + 1] for a batch of clouds held as concatenated arrays (Sec. 4.1).
     """
     if capacity is None:
         guess = max(48 * int(out_xyz.shape[0]), 1024)
         try:
-            return pcpp_build_triplets(in_xyz, out_xyz, radius, t, plan_flags, guess, buffers)
+            return pcpp_build_triplets(in_xyz, out_xyz, radius, t, plan_flags, guess, buffers, in_offsets, out_offsets)
         except PcppError as e:
             if e.code != ERR_CAPACITY:
                 raise
-            return pcpp_build_triplets(in_xyz, out_xyz, radius, t, plan_flags, e.needed, buffers)
+            return pcpp_build_triplets(in_xyz, out_xyz, radius, t, plan_flags, e.needed, buffers, in_offsets, out_offsets)
     L = library()
     assert in_xyz.is_cuda and out_xyz.is_cuda and in_xyz.dtype == torch.float32 and out_xyz.dtype == torch.float32
     assert in_xyz.is_contiguous() and out_xyz.is_contiguous()
@@ -189,11 +200,18 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
     if want_plan and (plan is None or plan.numel() < plan_bytes):
         plan = _bytes(plan_bytes, dev)
     n = _landing_word()
-    rc = L.pcpp_build_triplets(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, float(radius), int(t),
-                               _ptr(tri_o), _ptr(tri_i), _ptr(tri_k), cap, _ptr(seg),
-                               ctypes.cast(n.data_ptr(), ctypes.POINTER(ctypes.c_int64)),
-                               _ptr(plan) if want_plan else None, plan.numel() if want_plan else 0, plan_flags,
-                               _ptr(ws), ws.numel(), _stream())
+    n_batches = 1
+    if in_offsets is not None or out_offsets is not None:
+        assert in_offsets is not None and out_offsets is not None and in_offsets.is_cuda and out_offsets.is_cuda
+        assert in_offsets.dtype == torch.int32 and out_offsets.dtype == torch.int32
+        assert in_offsets.numel() == out_offsets.numel() >= 2
+        n_batches = in_offsets.numel() - 1
+    rc = L.pcpp_build_triplets_batched(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, _ptr(in_offsets), _ptr(out_offsets),
+                                       n_batches, float(radius), int(t),
+                                       _ptr(tri_o), _ptr(tri_i), _ptr(tri_k), cap, _ptr(seg),
+                                       ctypes.cast(n.data_ptr(), ctypes.POINTER(ctypes.c_int64)),
+                                       _ptr(plan) if want_plan else None, plan.numel() if want_plan else 0, plan_flags,
+                                       _ptr(ws), ws.numel(), _stream())
     nt = int(n[0])
     if rc == ERR_CAPACITY:
         err = PcppError(rc, f"capacity {cap} too small, need {nt}")
@@ -201,6 +219,21 @@ def pcpp_build_triplets(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: flo
         raise err
     _check(rc)
     return Triplets(tri_o[:nt], tri_i[:nt], tri_k[:nt], seg[:K + 1], nt, n_in, n_out, t, plan, plan_flags & PLAN_MASK)
+
+
+def pcpp_voxel_subsample(xyz: torch.Tensor, pitch: float) -> torch.Tensor:
+    """Voxel-grid down-sampling that keeps original coordinates (Sec. 4.1): indices (ascending, int32) of the
+    lowest-index point of every occupied voxel of the given pitch."""
+    L = library()
+    assert xyz.is_cuda and xyz.is_contiguous() and xyz.dtype == torch.float32
+    n = int(xyz.shape[0])
+    kept = torch.empty(max(n, 1), dtype=torch.int32, device=xyz.device)
+    ws = _bytes(L.pcpp_voxel_subsample_workspace_bytes(n), xyz.device)
+    cnt = _landing_word()
+    _check(L.pcpp_voxel_subsample(_ptr(xyz), n, float(pitch), _ptr(kept),
+                                  ctypes.cast(cnt.data_ptr(), ctypes.POINTER(ctypes.c_int64)), _ptr(ws), ws.numel(),
+                                  _stream()))
+    return kept[:int(cnt[0])]
 
 
 def _plan_args(T: Triplets):

@@ -43,6 +43,54 @@ __device__ inline unsigned long long pack_key(int cx, int cy, int cz)
            (unsigned long long)(uint32_t)(cz + CELL_BIAS);
 }
 
+// Which cloud of a batch a point belongs to: the largest b with off[b] <= idx (off has n_batches + 1 entries).
+__device__ inline int find_batch(const int32_t *__restrict__ off, int n_batches, int idx)
+{
+    int lo = 0, hi = n_batches - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= idx) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Voxel of a coordinate in a global voxelisation of pitch v (voxel mode): floor(p / v) in binary64.
+__device__ inline double voxel_of(float p, double v) { return floor(__ddiv_rn((double)p, v)); }
+
+__device__ inline int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+
+// How points map to cells of the hashed grid.  Ball mode: cells of pitch 1 / inv_g (a hair above the radius).
+// Voxel mode: cells of hp = max(h, 1) voxels per axis, so that voxels at most h apart lie in adjacent cells.
+// With batches the cloud's number is mixed into the key: equal keys of different clouds are possible but harmless,
+// because a centre only accepts candidates of its own cloud (their index range) and never probes two cells whose
+// keys the mixing could make equal (it is a bijection within one cloud).
+struct GridMap {
+    double inv_g;
+    double vox;       // voxel pitch, voxel mode only
+    int hp;
+    int voxel_mode;
+};
+
+__device__ inline void grid_cell3(float fx, float fy, float fz, const GridMap &m, int &gx, int &gy, int &gz)
+{
+    if (m.voxel_mode) {
+        const double lim = CELL_CLAMP * (double)m.hp;
+        gx = floor_div((int)fmin(fmax(voxel_of(fx, m.vox), -lim), lim), m.hp);
+        gy = floor_div((int)fmin(fmax(voxel_of(fy, m.vox), -lim), lim), m.hp);
+        gz = floor_div((int)fmin(fmax(voxel_of(fz, m.vox), -lim), lim), m.hp);
+    } else {
+        gx = grid_coord(fx, m.inv_g);
+        gy = grid_coord(fy, m.inv_g);
+        gz = grid_coord(fz, m.inv_g);
+    }
+}
+
+__device__ inline unsigned long long mix_batch(unsigned long long key, int batch)
+{
+    key ^= (unsigned long long)(batch + 1) * 0x9E3779B97F4A7C15ull;
+    return key == EMPTY_KEY ? key - 1ull : key;
+}
+
 // ---- hashed grid over the candidate set ------------------------------------------------------
 
 // empty table: no keys, zero populations (slots + 1 entries, the input of the prefix sum), zero cursors;
@@ -59,15 +107,18 @@ __global__ __launch_bounds__(256) void grid_clear(unsigned long long *__restrict
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < scan_words; i += stride) scan_status[i] = 0ull;
 }
 
-__global__ __launch_bounds__(256) void grid_insert(const float *__restrict__ xyz, int64_t n, double inv_g,
+__global__ __launch_bounds__(256) void grid_insert(const float *__restrict__ xyz, int64_t n, GridMap gm,
+                                                   const int32_t *__restrict__ batch_off, int n_batches,
                                                    unsigned long long *__restrict__ keys,
                                                    uint32_t *__restrict__ slot_cnt, uint32_t mask,
                                                    uint32_t *__restrict__ point_slot)
 {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n) return;
-    const unsigned long long key = pack_key(grid_coord(xyz[3 * p], inv_g), grid_coord(xyz[3 * p + 1], inv_g),
-                                            grid_coord(xyz[3 * p + 2], inv_g));
+    int gx, gy, gz;
+    grid_cell3(xyz[3 * p], xyz[3 * p + 1], xyz[3 * p + 2], gm, gx, gy, gz);
+    unsigned long long key = pack_key(gx, gy, gz);
+    if (batch_off) key = mix_batch(key, find_batch(batch_off, n_batches, (int)p));
     uint32_t slot = hash_key(key) & mask;
     // the table has at least twice as many slots as points, so an empty slot is always reached
     for (;;) {
@@ -97,14 +148,21 @@ struct GridView {
     const uint32_t *slot_start;   // [slots + 1]
     const float4 *pts;            // candidates grouped by grid cell; .w carries the original index
     uint32_t mask;
-    double inv_g;
+    GridMap map;
 };
 
+// Ball mode (Sec. 3.2 "Definition"): R, r2, inv_cell.  Voxel mode (the degraded operator of Sec. 3.2, "Voxel
+// Convolution as a Special Case"): neighbours are the points whose voxel differs from the centre's by at most
+// h = (t - 1) / 2 along every axis, the cell is the voxel offset (input minus output) plus h.
+// Batches: c_off / d_off are the offsets of the clouds in the centre set and in the candidate set.
 struct QueryParams {
-    double R;         // (double)radius
+    double R;         // (double)radius, or the voxel pitch
     double r2;        // R * R
     double inv_cell;  // t / (2 R)
     int t;
+    int voxel_mode, h;
+    const int32_t *c_off, *d_off;
+    int n_batches;
 };
 
 __device__ inline uint32_t wave_incl_scan_u32(uint32_t v, int lane)
@@ -121,22 +179,32 @@ __device__ inline uint32_t wave_incl_scan_u32(uint32_t v, int lane)
 // Every method must be called by all 64 lanes of the wave (it uses cross-lane reads).
 template <bool SWAP>
 struct Candidates {
-    double cx, cy, cz;       // centre coordinate
+    double cx, cy, cz;       // centre coordinate (ball mode) or its voxel (voxel mode)
     uint32_t my_start;       // lane j: first candidate of stencil cell j
     uint32_t my_excl;        // lane j: candidates in cells before j
     uint32_t total;
+    int d_lo, d_hi;          // candidates of the centre's own cloud: indices [d_lo, d_hi)
 
-    __device__ inline void open(const float *__restrict__ centres, int64_t a, const GridView &g, int lane)
+    __device__ inline void open(const float *__restrict__ centres, int64_t a, const GridView &g, const QueryParams &q,
+                                int lane)
     {
         const float fx = centres[3 * a], fy = centres[3 * a + 1], fz = centres[3 * a + 2];
-        cx = (double)fx; cy = (double)fy; cz = (double)fz;
+        if (q.voxel_mode) { cx = voxel_of(fx, q.R); cy = voxel_of(fy, q.R); cz = voxel_of(fz, q.R); }
+        else { cx = (double)fx; cy = (double)fy; cz = (double)fz; }
+        int batch = 0;
+        d_lo = 0; d_hi = 0x7fffffff;
+        if (q.c_off) {
+            batch = find_batch(q.c_off, q.n_batches, (int)a);
+            d_lo = q.d_off[batch]; d_hi = q.d_off[batch + 1];
+        }
         uint32_t cnt = 0;
         my_start = 0;
         if (lane < 27) {
-            const int gx = grid_coord(fx, g.inv_g) + lane / 9 - 1;
-            const int gy = grid_coord(fy, g.inv_g) + (lane / 3) % 3 - 1;
-            const int gz = grid_coord(fz, g.inv_g) + lane % 3 - 1;
-            const unsigned long long key = pack_key(gx, gy, gz);
+            int gx, gy, gz;
+            grid_cell3(fx, fy, fz, g.map, gx, gy, gz);
+            gx += lane / 9 - 1; gy += (lane / 3) % 3 - 1; gz += lane % 3 - 1;
+            unsigned long long key = pack_key(gx, gy, gz);
+            if (q.c_off) key = mix_batch(key, batch);
             uint32_t slot = hash_key(key) & g.mask;
             for (;;) {
                 const unsigned long long kk = g.keys[slot];
@@ -183,12 +251,25 @@ struct Candidates {
         if (in_range) {
             const float4 p = g.pts[s + (id - e)];
             b = __float_as_int(p.w);
+            if (q.voxel_mode) {
+                // voxel offset, input minus output; exact small integers in binary64
+                const double vx = voxel_of(p.x, q.R), vy = voxel_of(p.y, q.R), vz = voxel_of(p.z, q.R);
+                const double ox = SWAP ? cx - vx : vx - cx, oy = SWAP ? cy - vy : vy - cy, oz = SWAP ? cz - vz : vz - cz;
+                const double hh = (double)q.h;
+                hit = fabs(ox) <= hh && fabs(oy) <= hh && fabs(oz) <= hh && b >= d_lo && b < d_hi;
+                if (hit) {
+                    const int ix = (int)ox, iy = (int)oy, iz = (int)oz;
+                    k = ((ix + q.h) * q.t + iy + q.h) * q.t + iz + q.h;
+                    if constexpr (MIRROR) k2 = ((q.h - ix) * q.t + q.h - iy) * q.t + q.h - iz;
+                }
+                return hit;
+            }
             // d = input - output, in binary64, no contraction
             const double dx = SWAP ? __dsub_rn(cx, (double)p.x) : __dsub_rn((double)p.x, cx);
             const double dy = SWAP ? __dsub_rn(cy, (double)p.y) : __dsub_rn((double)p.y, cy);
             const double dz = SWAP ? __dsub_rn(cz, (double)p.z) : __dsub_rn((double)p.z, cz);
             const double d2 = __dadd_rn(__dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy)), __dmul_rn(dz, dz));
-            hit = d2 <= q.r2;
+            hit = d2 <= q.r2 && b >= d_lo && b < d_hi;
             const int tm1 = q.t - 1;
             const double ux = floor(__dmul_rn(__dadd_rn(dx, q.R), q.inv_cell));
             const double uy = floor(__dmul_rn(__dadd_rn(dy, q.R), q.inv_cell));
@@ -251,7 +332,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
         const int64_t a = tile * TILE + al;        // slot; the tables and lists are indexed by it
         if (a >= n_centres) break;                 // wave-uniform
         Candidates<SWAP> c;
-        c.open(centres, perm ? (int64_t)perm[a] : a, g, lane);
+        c.open(centres, perm ? (int64_t)perm[a] : a, g, q, lane);
         uint32_t filled = 0;
         for (uint32_t base = 0; base < c.total; base += 64) {
             int b, k, k2;
@@ -467,7 +548,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                 }
             } else {
                 Candidates<SWAP> &c = cand[0];
-                c.open(centres, ac, g, lane);
+                c.open(centres, ac, g, q, lane);
                 for (uint32_t base = 0; base < c.total; base += 64) {
                     int b, k;
                     if (c.fetch(base + lane, g, q, b, k)) {
@@ -538,7 +619,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
         }
         if (n == 0) continue;                  // wave-uniform
         Candidates<SWAP> &c = cand[0];
-        c.open(centres, ac, g, lane);
+        c.open(centres, ac, g, q, lane);
         if (n <= SMALL_LIST && n <= (uint32_t)list_cap) {
             // few neighbours: one flat list of (cell, index) keys in arrival order, rank by comparing all pairs
             unsigned long long *keys = reinterpret_cast<unsigned long long *>(list);
@@ -635,6 +716,58 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
     }
 }
 
+// ---- voxel-grid down-sampling that keeps original coordinates (Sec. 4.1) ----------------------------------------
+// One point per occupied voxel of pitch v: the one with the lowest index.  The voxels go through the same kind of
+// hash table as the search grid; every slot keeps the lowest index inserted into it.
+
+__global__ __launch_bounds__(256) void sub_clear(unsigned long long *__restrict__ keys, int *__restrict__ lowest,
+                                                 int64_t slots, unsigned long long *__restrict__ zero_from,
+                                                 int64_t zero_words)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < slots; i += stride) {
+        keys[i] = EMPTY_KEY;
+        lowest[i] = 0x7fffffff;
+    }
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < zero_words; i += stride) zero_from[i] = 0ull;
+}
+
+__global__ __launch_bounds__(256) void sub_insert(const float *__restrict__ xyz, int64_t n, double v,
+                                                  unsigned long long *__restrict__ keys, int *__restrict__ lowest,
+                                                  uint32_t mask, uint32_t *__restrict__ point_slot)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    int c[3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a) c[a] = (int)fmin(fmax(voxel_of(xyz[3 * p + a], v), -CELL_CLAMP), CELL_CLAMP);
+    const unsigned long long key = pack_key(c[0], c[1], c[2]);
+    uint32_t slot = hash_key(key) & mask;
+    for (;;) {
+        unsigned long long prev = atomicCAS(&keys[slot], EMPTY_KEY, key);
+        if (prev == EMPTY_KEY || prev == key) break;
+        slot = (slot + 1) & mask;
+    }
+    atomicMin(&lowest[slot], (int)p);
+    point_slot[p] = slot;
+}
+
+__global__ __launch_bounds__(256) void sub_flag(int64_t n, const int *__restrict__ lowest,
+                                                const uint32_t *__restrict__ point_slot, uint32_t *__restrict__ flag)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n) flag[p] = lowest[point_slot[p]] == (int)p ? 1u : 0u;
+}
+
+// pos = exclusive prefix sum of the flags, computed in place over them: a point is kept iff pos[p + 1] > pos[p]
+__global__ __launch_bounds__(256) void sub_scatter(int64_t n, const uint32_t *__restrict__ pos, int32_t *__restrict__ kept,
+                                                   const uint32_t *__restrict__ err)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n || *err) return;
+    if (pos[p + 1] != pos[p]) kept[pos[p]] = (int32_t)p;
+}
+
 // ---- host side ------------------------------------------------------------------------------
 
 struct GridScratch {
@@ -646,6 +779,27 @@ int64_t grid_slots(int64_t n)
 {
     int64_t s = 64;
     while (s < 2 * n) s <<= 1;
+    return s;
+}
+
+struct SubScratch {
+    size_t err_off, total_off, scan_off, keys_off, lowest_off, slot_off, flag_off, end;
+    int64_t slots;
+};
+
+SubScratch sub_scratch(int64_t n)
+{
+    SubScratch s;
+    s.slots = grid_slots(n);
+    size_t off = 0;
+    s.err_off = off;    off += 256;
+    s.total_off = off;  off += 256;
+    s.scan_off = off;   off += scan_scratch_bytes(n > 0 ? n : 1);
+    s.keys_off = off;   off += align_up((size_t)s.slots * 8);
+    s.lowest_off = off; off += align_up((size_t)s.slots * 4);
+    s.slot_off = off;   off += align_up((size_t)(n > 0 ? n : 1) * 4);
+    s.flag_off = off;   off += align_up((size_t)(n + 1) * 4);
+    s.end = off;
     return s;
 }
 
@@ -732,8 +886,9 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity 
 // scan_scratch: the status words of this grid's prefix sum.  clear_words > 0: the first grid of a build, whose
 // clearing kernel also zeroes the error word and the status words of all the build's prefix sums (they follow
 // the error word in the workspace).
-int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridScratch &gs, void *scan_scratch,
-               unsigned long long *clear_from, int64_t clear_words, uint32_t *err, GridView *view, hipStream_t stream)
+int build_grid(const float *xyz, int64_t n, const GridMap &gm, const int32_t *batch_off, int n_batches, char *ws,
+               const GridScratch &gs, void *scan_scratch, unsigned long long *clear_from, int64_t clear_words,
+               uint32_t *err, GridView *view, hipStream_t stream)
 {
     auto *keys = reinterpret_cast<unsigned long long *>(ws + gs.keys_off);
     auto *cnt = reinterpret_cast<uint32_t *>(ws + gs.cnt_off);
@@ -749,7 +904,8 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
     }
     if (n > 0) {
         const unsigned blocks = (unsigned)ceil_div(n, 256);
-        grid_insert<<<blocks, 256, 0, stream>>>(xyz, n, inv_g, keys, cnt, (uint32_t)(gs.slots - 1), point_slot);
+        grid_insert<<<blocks, 256, 0, stream>>>(xyz, n, gm, batch_off, n_batches, keys, cnt, (uint32_t)(gs.slots - 1),
+                                                point_slot);
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if ((rc = scan_exclusive_u32(cnt, cnt, gs.slots, scan_scratch, nullptr, err, stream)) != PCPP_OK) return rc;
@@ -762,7 +918,7 @@ int build_grid(const float *xyz, int64_t n, double inv_g, char *ws, const GridSc
     view->slot_start = cnt;
     view->pts = pts;
     view->mask = (uint32_t)(gs.slots - 1);
-    view->inv_g = inv_g;
+    view->map = gm;
     return PCPP_OK;
 }
 
@@ -829,7 +985,26 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
                         void *plan, size_t plan_bytes, int plan_flags,
                         void *workspace, size_t workspace_bytes, void *stream_)
 {
+    return pcpp_build_triplets_batched(in_xyz, n_in, out_xyz, n_out, nullptr, nullptr, 1, radius, t, tri_o, tri_i, tri_k,
+                                       capacity, seg_offsets, n_triplets, plan, plan_bytes, plan_flags, workspace,
+                                       workspace_bytes, stream_);
+}
+
+int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *out_xyz, int64_t n_out,
+                                const int32_t *in_batch_offsets, const int32_t *out_batch_offsets, int n_batches,
+                                float radius, int t,
+                                int32_t *tri_o, int32_t *tri_i, int32_t *tri_k, int64_t capacity,
+                                int64_t *seg_offsets, int64_t *n_triplets,
+                                void *plan, size_t plan_bytes, int plan_flags,
+                                void *workspace, size_t workspace_bytes, void *stream_)
+{
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (n_batches < 1 || n_batches > 65536 || ((in_batch_offsets == nullptr) != (out_batch_offsets == nullptr)) ||
+        (n_batches > 1 && !in_batch_offsets)) {
+        set_error("pcpp_build_triplets_batched: n_batches must be in 1..65536 and both offset arrays given (or neither, "
+                  "for one cloud)");
+        return PCPP_ERR_INVALID_ARG;
+    }
     if (n_in < 0 || n_out < 0 || (n_in > 0 && !in_xyz) || (n_out > 0 && !out_xyz) || !n_triplets) {
         set_error("pcpp_build_triplets: null pointer or negative size");
         return PCPP_ERR_INVALID_ARG;
@@ -857,8 +1032,13 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         return PCPP_ERR_INVALID_ARG;
     }
     const int test_flags = plan_flags & (PCPP_BUILD_TEST_SHORT_LISTS | PCPP_BUILD_TEST_WIDE_KEYS);
-    if (plan_flags & ~(PLAN_FLAG_MASK | PCPP_BUILD_TEST_SHORT_LISTS | PCPP_BUILD_TEST_WIDE_KEYS)) {
+    if (plan_flags & ~(PLAN_FLAG_MASK | PCPP_BUILD_TEST_SHORT_LISTS | PCPP_BUILD_TEST_WIDE_KEYS | PCPP_BUILD_VOXEL)) {
         set_error("pcpp_build_triplets: unknown bits in plan_flags");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    const bool voxel = (plan_flags & PCPP_BUILD_VOXEL) != 0;
+    if (voxel && t % 2 == 0) {
+        set_error("pcpp_build_triplets: the voxel operator needs an odd t (a centre voxel)");
         return PCPP_ERR_INVALID_ARG;
     }
     plan_flags &= PLAN_FLAG_MASK;
@@ -905,17 +1085,29 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     // grid pitch a hair above r so that, with the binary64 cell computation, any accepted pair lies
     // in adjacent grid cells (27-cell stencil is conservative)
     const double R = (double)radius;
-    const double inv_g = 1.0 / (R * (1.0 + 1.0 / 1048576.0));
+    GridMap gm;
+    gm.inv_g = 1.0 / (R * (1.0 + 1.0 / 1048576.0));
+    gm.vox = R;
+    gm.hp = (t - 1) / 2 > 1 ? (t - 1) / 2 : 1;
+    gm.voxel_mode = voxel ? 1 : 0;
     QueryParams q;
     q.R = R;
     q.r2 = R * R;
     q.inv_cell = (double)t / (2.0 * R);
     q.t = t;
+    q.voxel_mode = voxel ? 1 : 0;
+    q.h = (t - 1) / 2;
+    q.c_off = out_batch_offsets;         // forward orientation: centres = outputs, candidates = inputs
+    q.d_off = in_batch_offsets;
+    q.n_batches = n_batches;
+    QueryParams qs = q;                  // roles swapped: centres = inputs, candidates = outputs
+    qs.c_off = in_batch_offsets;
+    qs.d_off = out_batch_offsets;
 
     int rc;
     GridView grid_in;
     // the clearing kernel of the first grid zeroes the error word, the total and all status words (contiguous)
-    if ((rc = build_grid(in_xyz, n_in, inv_g, ws, bs.grid_in, scan_scratch(SCAN_GRID_IN),
+    if ((rc = build_grid(in_xyz, n_in, gm, in_batch_offsets, n_batches, ws, bs.grid_in, scan_scratch(SCAN_GRID_IN),
                          reinterpret_cast<unsigned long long *>(ws + bs.err_off),
                          (int64_t)((512 + N_SCANS * bs.scan_stride) / sizeof(unsigned long long)), err, &grid_in,
                          stream)) != PCPP_OK)
@@ -938,7 +1130,7 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     const bool want_plan = plan && !count_only;
     const bool want_bwd = want_plan && (plan_flags & PCPP_PLAN_BWD_INPUT);
     const bool spatial = want_plan && (plan_flags & PCPP_PLAN_SPATIAL);
-    const bool self = out_xyz == in_xyz && n_out == n_in;
+    const bool self = out_xyz == in_xyz && n_out == n_in && in_batch_offsets == out_batch_offsets;
 
     // A cloud queried against itself: one pass counts both sides of the plan (while two [K][64] tables fit the
     // LDS that one block may allocate, beside the lists).
@@ -1036,8 +1228,8 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
     // ---- the plan's sides ---------------------------------------------------------------------------------------
     GridView grid_out = grid_in;
     if (want_bwd && !self) {
-        if ((rc = build_grid(out_xyz, n_out, inv_g, ws, bs.grid_out, scan_scratch(SCAN_GRID_OUT), nullptr, 0, err,
-                             &grid_out, stream)) != PCPP_OK)
+        if ((rc = build_grid(out_xyz, n_out, gm, out_batch_offsets, n_batches, ws, bs.grid_out, scan_scratch(SCAN_GRID_OUT),
+                             nullptr, 0, err, &grid_out, stream)) != PCPP_OK)
             return rc;
     }
     const int32_t *perm_o = nullptr, *perm_i = nullptr;
@@ -1088,14 +1280,14 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
         uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
         if (nt_i > 0 && !one_pass) {
             query_count<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
-                in_xyz, n_in, perm_i, grid_out, q, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
+                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
             PCPP_HIP_CHECK(hipGetLastError());
         }
         if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch(SCAN_BWD_SIDE), nullptr, err, stream)) != PCPP_OK)
             return rc;
         if (nt_i > 0) {
             query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(
-                in_xyz, n_in, perm_i, grid_out, q, K, nt_i, b_cnt, b_ptr,
+                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, b_cnt, b_ptr,
                 FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.bwd.gather_index, tail_cap}, b_runs, list_cap,
                 b_hits, bs.bwd_stride, nullptr, pack_ok, err);
             PCPP_HIP_CHECK(hipGetLastError());
@@ -1114,6 +1306,82 @@ int pcpp_build_triplets(const float *in_xyz, int64_t n_in, const float *out_xyz,
             return PCPP_ERR_WORKSPACE;
         }
     }
+    return PCPP_OK;
+}
+
+size_t pcpp_voxel_subsample_workspace_bytes(int64_t n)
+{
+    if (n < 0 || n >= INT32_MAX) return 0;
+    return sub_scratch(n).end;
+}
+
+int pcpp_voxel_subsample(const float *xyz, int64_t n, float pitch, int32_t *kept, int64_t *n_kept, void *workspace,
+                         size_t workspace_bytes, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (n < 0 || (n > 0 && (!xyz || !kept)) || !n_kept) {
+        set_error("pcpp_voxel_subsample: null pointer or negative size");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    if (n >= INT32_MAX) {
+        set_error("pcpp_voxel_subsample: point count must be below 2^31");
+        return PCPP_ERR_UNSUPPORTED;
+    }
+    if (!(pitch > 0.0f) || !isfinite(pitch)) {
+        set_error("pcpp_voxel_subsample: pitch must be finite and positive");
+        return PCPP_ERR_INVALID_ARG;
+    }
+    const SubScratch ss = sub_scratch(n);
+    if (!workspace || workspace_bytes < ss.end || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
+        set_error("pcpp_voxel_subsample: workspace missing, misaligned or smaller than %zu bytes", ss.end);
+        return PCPP_ERR_WORKSPACE;
+    }
+    *n_kept = 0;
+    if (n == 0) return PCPP_OK;
+    char *ws = static_cast<char *>(workspace);
+    auto *keys = reinterpret_cast<unsigned long long *>(ws + ss.keys_off);
+    int *lowest = reinterpret_cast<int *>(ws + ss.lowest_off);
+    auto *point_slot = reinterpret_cast<uint32_t *>(ws + ss.slot_off);
+    auto *flag = reinterpret_cast<uint32_t *>(ws + ss.flag_off);
+    auto *err = reinterpret_cast<uint32_t *>(ws + ss.err_off);
+    unsigned long long *total_dev = reinterpret_cast<unsigned long long *>(ws + ss.total_off);
+    bool pinned = false;
+    {
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, n_kept) == hipSuccess && attr.type == hipMemoryTypeHost && attr.devicePointer) {
+            total_dev = static_cast<unsigned long long *>(attr.devicePointer);
+            pinned = true;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    int64_t blocks = ceil_div(ss.slots, 256);
+    if (blocks > 4096) blocks = 4096;
+    // the error word, the landing word and the prefix sum's status words are contiguous at the start of the workspace
+    sub_clear<<<(unsigned)blocks, 256, 0, stream>>>(keys, lowest, ss.slots, reinterpret_cast<unsigned long long *>(ws),
+                                                    (int64_t)(ss.keys_off / sizeof(unsigned long long)));
+    const unsigned pb = (unsigned)ceil_div(n, 256);
+    sub_insert<<<pb, 256, 0, stream>>>(xyz, n, (double)pitch, keys, lowest, (uint32_t)(ss.slots - 1), point_slot);
+    sub_flag<<<pb, 256, 0, stream>>>(n, lowest, point_slot, flag);
+    PCPP_HIP_CHECK(hipGetLastError());
+    int rc;
+    if ((rc = scan_exclusive_u32(flag, flag, n, ws + ss.scan_off, total_dev, err, stream)) != PCPP_OK) return rc;
+    sub_scatter<<<pb, 256, 0, stream>>>(n, flag, kept, err);
+    PCPP_HIP_CHECK(hipGetLastError());
+    unsigned long long total = 0;
+    if (pinned) {
+        PCPP_HIP_CHECK(hipStreamSynchronize(stream));
+        total = *reinterpret_cast<volatile unsigned long long *>(n_kept);
+    } else {
+        PCPP_HIP_CHECK(hipMemcpyAsync(&total, total_dev, sizeof(total), hipMemcpyDeviceToHost, stream));
+        PCPP_HIP_CHECK(hipStreamSynchronize(stream));
+    }
+    if (total == ~0ull) {
+        *n_kept = 0;
+        set_error("pcpp_voxel_subsample: a wait inside a device-wide prefix sum ran out");
+        return PCPP_ERR_HIP;
+    }
+    *n_kept = (int64_t)total;
     return PCPP_OK;
 }
 
