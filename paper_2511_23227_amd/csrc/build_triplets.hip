@@ -177,7 +177,9 @@ __device__ inline uint32_t wave_incl_scan_u32(uint32_t v, int lane)
 
 // Candidates of one centre, held across the lanes of a wave: lane j < 27 owns stencil cell j.
 // Every method must be called by all 64 lanes of the wave (it uses cross-lane reads).
-template <bool SWAP>
+// EXT: the voxel operator and batches of clouds are compiled in (the plain search kernels, which are bound by
+// instruction issue, do without their tests).
+template <bool SWAP, bool EXT>
 struct Candidates {
     double cx, cy, cz;       // centre coordinate (ball mode) or its voxel (voxel mode)
     uint32_t my_start;       // lane j: first candidate of stencil cell j
@@ -189,11 +191,11 @@ struct Candidates {
                                 int lane)
     {
         const float fx = centres[3 * a], fy = centres[3 * a + 1], fz = centres[3 * a + 2];
-        if (q.voxel_mode) { cx = voxel_of(fx, q.R); cy = voxel_of(fy, q.R); cz = voxel_of(fz, q.R); }
+        if (EXT && q.voxel_mode) { cx = voxel_of(fx, q.R); cy = voxel_of(fy, q.R); cz = voxel_of(fz, q.R); }
         else { cx = (double)fx; cy = (double)fy; cz = (double)fz; }
         int batch = 0;
         d_lo = 0; d_hi = 0x7fffffff;
-        if (q.c_off) {
+        if (EXT && q.c_off) {
             batch = find_batch(q.c_off, q.n_batches, (int)a);
             d_lo = q.d_off[batch]; d_hi = q.d_off[batch + 1];
         }
@@ -201,10 +203,14 @@ struct Candidates {
         my_start = 0;
         if (lane < 27) {
             int gx, gy, gz;
-            grid_cell3(fx, fy, fz, g.map, gx, gy, gz);
+            if constexpr (EXT) {
+                grid_cell3(fx, fy, fz, g.map, gx, gy, gz);
+            } else {
+                gx = grid_coord(fx, g.map.inv_g); gy = grid_coord(fy, g.map.inv_g); gz = grid_coord(fz, g.map.inv_g);
+            }
             gx += lane / 9 - 1; gy += (lane / 3) % 3 - 1; gz += lane % 3 - 1;
             unsigned long long key = pack_key(gx, gy, gz);
-            if (q.c_off) key = mix_batch(key, batch);
+            if (EXT && q.c_off) key = mix_batch(key, batch);
             uint32_t slot = hash_key(key) & g.mask;
             for (;;) {
                 const unsigned long long kk = g.keys[slot];
@@ -251,7 +257,7 @@ struct Candidates {
         if (in_range) {
             const float4 p = g.pts[s + (id - e)];
             b = __float_as_int(p.w);
-            if (q.voxel_mode) {
+            if (EXT && q.voxel_mode) {
                 // voxel offset, input minus output; exact small integers in binary64
                 const double vx = voxel_of(p.x, q.R), vy = voxel_of(p.y, q.R), vz = voxel_of(p.z, q.R);
                 const double ox = SWAP ? cx - vx : vx - cx, oy = SWAP ? cy - vy : vy - cy, oz = SWAP ? cz - vz : vz - cz;
@@ -269,7 +275,7 @@ struct Candidates {
             const double dy = SWAP ? __dsub_rn(cy, (double)p.y) : __dsub_rn((double)p.y, cy);
             const double dz = SWAP ? __dsub_rn(cz, (double)p.z) : __dsub_rn((double)p.z, cz);
             const double d2 = __dadd_rn(__dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy)), __dmul_rn(dz, dz));
-            hit = d2 <= q.r2 && b >= d_lo && b < d_hi;
+            hit = d2 <= q.r2 && (!EXT || (b >= d_lo && b < d_hi));
             const int tm1 = q.t - 1;
             const double ux = floor(__dmul_rn(__dadd_rn(dx, q.R), q.inv_cell));
             const double uy = floor(__dmul_rn(__dadd_rn(dy, q.R), q.inv_cell));
@@ -311,7 +317,7 @@ struct CountOut {
     uint32_t *tile_cnt, *tile_k_cnt, *hits;
 };
 
-template <bool SWAP, bool BOTH>
+template <bool SWAP, bool BOTH, bool EXT>
 __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__restrict__ centres, int64_t n_centres,
                                                               const int32_t *__restrict__ perm,
                                                               GridView g, QueryParams q, int K, int64_t n_tiles,
@@ -331,7 +337,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
     for (int al = wave; al < TILE; al += SEARCH_WAVES) {
         const int64_t a = tile * TILE + al;        // slot; the tables and lists are indexed by it
         if (a >= n_centres) break;                 // wave-uniform
-        Candidates<SWAP> c;
+        Candidates<SWAP, EXT> c;
         c.open(centres, perm ? (int64_t)perm[a] : a, g, q, lane);
         uint32_t filled = 0;
         for (uint32_t base = 0; base < c.total; base += 64) {
@@ -419,7 +425,7 @@ struct Emit {
     }
 };
 
-template <bool SWAP>
+template <bool SWAP, bool EXT>
 __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__restrict__ centres, int64_t n_centres,
                                                              const int32_t *__restrict__ perm,
                                                              GridView g, QueryParams q, int K, int64_t n_tiles,
@@ -467,7 +473,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
     // A centre whose neighbours the count pass left in `hits` needs no second search.
     constexpr int PER_WAVE = TILE / SEARCH_WAVES;
     const uint32_t reuse_max = hits ? (hit_stride < KEEP_MAX ? hit_stride : KEEP_MAX) : 0u;
-    Candidates<SWAP> cand[1];
+    Candidates<SWAP, EXT> cand[1];
     uint32_t n_of[PER_WAVE];
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
@@ -547,7 +553,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
                     list[(old >> 16) + (old & 0xffffu)] = key;
                 }
             } else {
-                Candidates<SWAP> &c = cand[0];
+                Candidates<SWAP, EXT> &c = cand[0];
                 c.open(centres, ac, g, q, lane);
                 for (uint32_t base = 0; base < c.total; base += 64) {
                     int b, k;
@@ -618,7 +624,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_fill(const float *__r
             }
         }
         if (n == 0) continue;                  // wave-uniform
-        Candidates<SWAP> &c = cand[0];
+        Candidates<SWAP, EXT> &c = cand[0];
         c.open(centres, ac, g, q, lane);
         if (n <= SMALL_LIST && n <= (uint32_t)list_cap) {
             // few neighbours: one flat list of (cell, index) keys in arrival order, rank by comparing all pairs
@@ -1037,6 +1043,7 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
         return PCPP_ERR_INVALID_ARG;
     }
     const bool voxel = (plan_flags & PCPP_BUILD_VOXEL) != 0;
+    const bool ext = voxel || in_batch_offsets != nullptr;     // the search kernels with the variants compiled in
     if (voxel && t % 2 == 0) {
         set_error("pcpp_build_triplets: the voxel operator needs an odd t (a centre voxel)");
         return PCPP_ERR_INVALID_ARG;
@@ -1120,12 +1127,16 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
     const int pack_ok = !wide_keys && K <= 256 && n_in < (1 << HIT_INDEX_BITS) && n_out < (1 << HIT_INDEX_BITS);
     if (lds > (size_t)32 * 1024) {
         // large t: the per-tile table plus the neighbour lists exceed the default dynamic LDS limit
-        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_count<false, false>), lds)) != PCPP_OK) return rc;
-        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_count<true, false>), lds)) != PCPP_OK) return rc;
+        if ((rc = raise_lds_limit(ext ? reinterpret_cast<const void *>(&query_count<false, false, true>)
+                                      : reinterpret_cast<const void *>(&query_count<false, false, false>), lds)) != PCPP_OK) return rc;
+        if ((rc = raise_lds_limit(ext ? reinterpret_cast<const void *>(&query_count<true, false, true>)
+                                      : reinterpret_cast<const void *>(&query_count<true, false, false>), lds)) != PCPP_OK) return rc;
     }
     if (lds_fill > (size_t)32 * 1024) {
-        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_fill<false>), lds_fill)) != PCPP_OK) return rc;
-        if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_fill<true>), lds_fill)) != PCPP_OK) return rc;
+        if ((rc = raise_lds_limit(ext ? reinterpret_cast<const void *>(&query_fill<false, true>)
+                                      : reinterpret_cast<const void *>(&query_fill<false, false>), lds_fill)) != PCPP_OK) return rc;
+        if ((rc = raise_lds_limit(ext ? reinterpret_cast<const void *>(&query_fill<true, true>)
+                                      : reinterpret_cast<const void *>(&query_fill<true, false>), lds_fill)) != PCPP_OK) return rc;
     }
     const bool want_plan = plan && !count_only;
     const bool want_bwd = want_plan && (plan_flags & PCPP_PLAN_BWD_INPUT);
@@ -1140,7 +1151,8 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
         PCPP_HIP_CHECK(hipGetDevice(&dev));
         PCPP_HIP_CHECK(hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
         if (2 * lds + (size_t)2 * SEARCH_WAVES * KEEP_MAX * sizeof(uint32_t) + 1024 > (size_t)per_block) one_pass = false;
-        else if ((rc = raise_lds_limit(reinterpret_cast<const void *>(&query_count<false, true>), 2 * lds)) != PCPP_OK)
+        else if ((rc = raise_lds_limit(ext ? reinterpret_cast<const void *>(&query_count<false, true, true>)
+                                           : reinterpret_cast<const void *>(&query_count<false, true, false>), 2 * lds)) != PCPP_OK)
             return rc;
     }
 
@@ -1164,11 +1176,19 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
     if (nt_o > 0) {
         const CountOut fwd_out{count_only ? nullptr : f_cnt, f_ptr, f_hits};
         if (one_pass && !spatial)
-            query_count<false, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+            {
+                if (ext) query_count<false, true, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
                 out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+                else query_count<false, true, false><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+            }
         else
-            query_count<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+            {
+                if (ext) query_count<false, false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
                 out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+                else query_count<false, false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+            }
         PCPP_HIP_CHECK(hipGetLastError());
     }
     if ((rc = scan_exclusive_u32(f_ptr, f_off, (int64_t)K * nt_o, scan_scratch(SCAN_PUBLIC), total_dev, err, stream)) != PCPP_OK)
@@ -1216,9 +1236,14 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
     }
     if (nt_o > 0) {
         uint32_t *f_runs = fwd_direct ? reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off) : nullptr;
-        query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
+        {
+                if (ext) query_fill<false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
             out_xyz, n_out, nullptr, grid_in, q, K, nt_o, f_cnt, f_off, FillOut{tri_o, tri_i, tri_k, nullptr, -1, tri_cap},
             f_runs, list_cap, f_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
+                else query_fill<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
+            out_xyz, n_out, nullptr, grid_in, q, K, nt_o, f_cnt, f_off, FillOut{tri_o, tri_i, tri_k, nullptr, -1, tri_cap},
+            f_runs, list_cap, f_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
+            }
         PCPP_HIP_CHECK(hipGetLastError());
     } else {
         // no outputs: every run starts at 0
@@ -1256,20 +1281,34 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
         if (nt_o > 0) {
             const CountOut fwd_out{f_cnt, f_ptr, f_hits};
             if (one_pass)
-                query_count<false, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+                {
+                if (ext) query_count<false, true, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
                     out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+                else query_count<false, true, false><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+            }
             else
-                query_count<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+                {
+                if (ext) query_count<false, false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
                     out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+                else query_count<false, false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+            }
             PCPP_HIP_CHECK(hipGetLastError());
         }
         if ((rc = scan_exclusive_u32(f_ptr, sf_ptr, (int64_t)K * nt_o, scan_scratch(SCAN_FWD_SIDE), nullptr, err, stream)) != PCPP_OK)
             return rc;
         if (nt_o > 0) {
-            query_fill<false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
+            {
+                if (ext) query_fill<false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
                 out_xyz, n_out, perm_o, grid_in, q, K, nt_o, f_cnt, sf_ptr,
                 FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.fwd.gather_index, tail_cap},
                 reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off), list_cap, f_hits, bs.fwd_stride, nullptr, pack_ok, err);
+                else query_fill<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
+                out_xyz, n_out, perm_o, grid_in, q, K, nt_o, f_cnt, sf_ptr,
+                FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.fwd.gather_index, tail_cap},
+                reinterpret_cast<uint32_t *>(pb + pl.fwd.run_start_off), list_cap, f_hits, bs.fwd_stride, nullptr, pack_ok, err);
+            }
             PCPP_HIP_CHECK(hipGetLastError());
         }
     }
@@ -1279,17 +1318,27 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
         uint32_t *b_ptr = reinterpret_cast<uint32_t *>(pb + pl.bwd.tile_ptr_off);
         uint32_t *b_runs = reinterpret_cast<uint32_t *>(pb + pl.bwd.run_start_off);
         if (nt_i > 0 && !one_pass) {
-            query_count<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
+            {
+                if (ext) query_count<true, false, true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
                 in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
+                else query_count<true, false, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
+                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
+            }
             PCPP_HIP_CHECK(hipGetLastError());
         }
         if ((rc = scan_exclusive_u32(b_sum, b_ptr, (int64_t)K * nt_i, scan_scratch(SCAN_BWD_SIDE), nullptr, err, stream)) != PCPP_OK)
             return rc;
         if (nt_i > 0) {
-            query_fill<true><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(
+            {
+                if (ext) query_fill<true, true><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(
                 in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, b_cnt, b_ptr,
                 FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.bwd.gather_index, tail_cap}, b_runs, list_cap,
                 b_hits, bs.bwd_stride, nullptr, pack_ok, err);
+                else query_fill<true, false><<<(unsigned)nt_i, SEARCH_THREADS, lds_fill, stream>>>(
+                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, b_cnt, b_ptr,
+                FillOut{nullptr, nullptr, nullptr, pb + pl.tail_off, pl.bwd.gather_index, tail_cap}, b_runs, list_cap,
+                b_hits, bs.bwd_stride, nullptr, pack_ok, err);
+            }
             PCPP_HIP_CHECK(hipGetLastError());
         }
     }
