@@ -393,7 +393,10 @@ int launch(const MvmrArgs &a, hipStream_t stream)
 template <bool BF16, int C_SRC, int C_DST>
 int launch_k(const MvmrArgs &a, hipStream_t stream)
 {
-    return launch<BF16, C_SRC, C_DST, 2>(a, stream);
+    // (64 -> 128: one wave per block measured 10 % faster on the strided scene -- twice the blocks for a layer with
+    // few output points, and no partial sums to add)
+    if constexpr (BF16 && C_SRC == 64 && C_DST == 128) return launch<BF16, C_SRC, C_DST, 1>(a, stream);
+    else return launch<BF16, C_SRC, C_DST, 2>(a, stream);
 }
 
 }  // namespace

@@ -4,21 +4,26 @@
 // Eq. (1) is linear, so out[o] = sum_k W[k] S_k[o] with S_k[o] = the sum of x[i] over the (k, o) run.  A block owns
 // 128 consecutive slots of the plan's centre order (two tiles) and walks the kernel cells that hold a triplet for
 // any of them.  Per cell,
-//   producer waves (four, one per SIMD; each serves 32 centres) gather the source rows of their centres' runs --
-//       one 512-byte row per load instruction, lane <-> four channels -- add them up in fp32 on the vector ALUs,
-//       round each run's sum to bf16 once and store it as row `centre` of an LDS tile S[128][C_src];
+//   producer waves (four, one per SIMD) gather the source rows of the block's runs -- the cell's triplets of the
+//       block are one contiguous piece of the list, cut into four shares at run boundaries; one 512-byte row per
+//       load instruction, lane <-> four channels -- add them up in fp32 on the vector ALUs, round each run's sum to
+//       bf16 once and store it as row `centre` of an LDS tile S[128][C_src]; centres without a run get rows of zeros;
 //   consumer waves (four, one per SIMD; each owns 64 destination channels of all 128 centres, 128 accumulator
-//       registers) multiply the tile by their slice of W[k] on the matrix cores, acc += S . W[k]^T, in groups of 16
-//       centres; groups in which no centre has a triplet in the cell are skipped (inside a group that is not, the
-//       producers store rows of zeros for the centres without one).
+//       registers) multiply the whole tile by their slice of W[k] on the matrix cores, acc += S . W[k]^T, 256 MFMAs
+//       in one straight line.  Groups of 16 centres without a triplet in the cell are multiplied too: on this
+//       workload 5.4 of 8 groups have one, but a test-and-branch per group costs a wave more than the 64 cycles of
+//       the matrix pipe that it saves and leaves no static schedule.
 // The two run one cell apart on two LDS tiles, one barrier per cell: while the matrix cores work on cell j the
 // rows of cell j + 1 are in flight.  A consumer's W slice (64 x C_src of the 16.4 MB at K = 125) comes straight from
 // memory / L2 into registers in fragment order, three 32-channel chunks ahead of its use (a ring of four); nothing
-// but S goes through LDS.  A wave issues at most one instruction every four cycles, so the consumers' inner unit
-// (one group of 16 centres x 32 source channels: four MFMAs, 64 cycles of the matrix pipe) holds little else: a
-// test of the group's bit, the four MFMAs and one LDS read at a fixed offset that fetches the group's A piece of
-// the next chunk; all waiting is one explicit instruction per chunk.  Every destination row is accumulated in registers across all cells and written once by its owner: no
-// atomics, fixed summation order.
+// but S goes through LDS.  Every destination row is accumulated in registers across all cells and written once by
+// its owner: no atomics, fixed summation order.
+//
+// What bounds it: the matrix pipe needs 256 x 16 = 4096 cycles per cell; the consumer's loads of W and of S add
+// about 1500 (each is an instruction of the same in-order wave).  A producer spends about 70 cycles per row when
+// alone on its SIMD (10 vector instructions for the sums, two conversions, and a 512-byte LDS store that costs
+// 24) and about 105 beside a wave that issues MFMAs back to back, since both issue through the SIMD's vector
+// port; with the per-cell bookkeeping a producer's cell takes about as long as a consumer's.
 //
 // v_mfma_f32_16x16x32_bf16 (A: lane (M = l%16, g = l/16) holds A[M][8g .. 8g+7]; B: lane (N = l%16, g) holds
 // B[8g .. 8g+7][N]; D: lane l, register j -> M = 4g + j, N = l%16):
@@ -41,6 +46,7 @@ constexpr int PC_PROD = 4, PC_CONS = 4;           // producer and consumer waves
 constexpr int PC_THREADS = (PC_PROD + PC_CONS) * 64;
 constexpr int PC_GROUPS = PC_ROWS / 16;
 constexpr int PC_SLOTS = 32;                      // rows a producer wave keeps in flight
+constexpr int PC_STEP = 4;                        // rows are requested and added in groups of this many
 constexpr int NUM_XCD = 8;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -83,21 +89,6 @@ __device__ inline void mfma_16x16x32_acc(v4f &c, const v4u &a, const v4u &b)
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
-// One A piece from LDS.  The read is outside the compiler's bookkeeping of outstanding memory operations, and so
-// are the waits for it (lds_wait): a consumer keeps exactly one read per active group in flight, in the order in
-// which the pieces are used, so "all but the newest two have arrived" is enough whenever three or more groups are
-// active -- a count the compiler cannot know and would replace by a wait for everything.
-template <int OFFSET>
-__device__ inline void lds_read_piece(v4u &dst, uint32_t addr)
-{
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET));
-}
-template <int N>
-__device__ inline void lds_wait()
-{
-    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
-}
-
 template <int NCH, typename TOut>
 __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
                                                              TOut *__restrict__ dst, int64_t n_centres, int K,
@@ -111,10 +102,9 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     static_assert(C_SRC == 256, "a producer lane holds four channels: rows of 256 channels");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char *S = lds;                                                 // [2][PC_ROWS][SROW]
-    uint32_t *hasrun = reinterpret_cast<uint32_t *>(lds + 2 * SBUF);   // [2][4]: bit c of word p = centre 32 p + c has a run
-    uint32_t *rank_tab = hasrun + 8;                               // [PC_PROD][32]: a producer's centres with a run, in order
-    int *act = reinterpret_cast<int *>(rank_tab + PC_PROD * 32);   // active cells, act[MAX_K] = their number
-    constexpr uint32_t DUMMY_OFF = 2 * SBUF + (8 + PC_PROD * 32) * 4 + (MAX_K + 1) * 4 + 12;   // [PC_PROD][ROWB]: where rows
+    uint32_t *rank_tab = reinterpret_cast<uint32_t *>(lds + 2 * SBUF);   // [PC_PROD][PC_ROWS]: per producer, the block's centres with a run, in order
+    int *act = reinterpret_cast<int *>(rank_tab + PC_PROD * PC_ROWS);   // active cells, act[MAX_K] = their number
+    constexpr uint32_t DUMMY_OFF = 2 * SBUF + PC_PROD * PC_ROWS * 4 + (MAX_K + 1) * 4 + 12;   // [PC_PROD][ROWB]: where rows
     static_assert(DUMMY_OFF % 16 == 0, "alignment of the scratch rows");                       // past a list's end are stored
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t per_xcd = gridDim.x / NUM_XCD;
@@ -139,23 +129,67 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
 
     if (wave < PC_PROD) {
         // ------------------------------------------------------------------------------------------------
-        // producer: centres 32 p .. 32 p + 31 of the block
+        // producer.  The triplets of a cell that belong to the block's 128 centres are one contiguous piece of the
+        // list (consecutive tiles of one cell follow each other); the four producers cut it into quarters at run
+        // boundaries -- producer p takes the runs that start in the p-th quarter -- so that each adds up about the
+        // same number of rows whatever the distribution of the neighbours over the centres.  (The barrier at the end
+        // of a cell waits for the slowest of the four.)  Rows of zeros for centres without a run: producer p clears
+        // those among centres 32 p .. 32 p + 31.
         // ------------------------------------------------------------------------------------------------
         const int p = wave;
-        const int64_t tile = t0 + (p >> 1);
-        const bool pvalid = tile < side.n_tiles;                   // wave-uniform
-        const int64_t tl = pvalid ? tile : side.n_tiles - 1;
-        const int cl = (p & 1) * 32 + (lane & 31);                 // this lane's centre inside the tile (lanes 32.. repeat)
-        const uint32_t *runs = side.run_start + (size_t)tl * K * TILE + cl;
-        const uint32_t *tends = side.tile_ptr + tl + 1;
-        const bool last_in_tile = cl == TILE - 1;
+        const bool b_valid = t0 + 1 < side.n_tiles;                // the block's second tile exists (uniform)
+        const int64_t tile_b = b_valid ? t0 + 1 : t0;
+        const uint32_t *runs_a = side.run_start + (size_t)t0 * K * TILE + lane;
+        const uint32_t *runs_b = side.run_start + (size_t)tile_b * K * TILE + lane;
+        const uint32_t *tends_a = side.tile_ptr + t0 + 1, *tends_b = side.tile_ptr + tile_b + 1;
+        const bool last_in_tile = lane == TILE - 1;
         const __amdgpu_buffer_rsrc_t frs = make_rsrc(feat_, feat_bytes);
+        const unsigned long long below = (1ull << lane) - 1ull;
 
+        struct Bounds { uint32_t st_a, en_a, st_b, en_b; };        // lane <-> centre `lane` of tile a and of tile b
         // bounds of the runs of cell act[j] (clamped; steps past the end are masked by their callers)
-        auto load_bounds = [&](int j, uint32_t &st, uint32_t &en) {
+        auto load_bounds = [&](int j) -> Bounds {
             const int k = act[j < n_act ? j : (n_act > 0 ? n_act - 1 : 0)];
-            st = runs[(size_t)k * TILE];
-            en = last_in_tile ? tends[(size_t)k * side.n_tiles] : runs[(size_t)k * TILE + 1];
+            Bounds b;
+            b.st_a = runs_a[(size_t)k * TILE];
+            b.en_a = last_in_tile ? tends_a[(size_t)k * side.n_tiles] : runs_a[(size_t)k * TILE + 1];
+            b.st_b = runs_b[(size_t)k * TILE];
+            b.en_b = last_in_tile ? tends_b[(size_t)k * side.n_tiles] : runs_b[(size_t)k * TILE + 1];
+            return b;
+        };
+        struct Share { uint32_t first, n, rank; };                 // this producer's triplets and the rank of its first run
+        auto share_of = [&](const Bounds &b) -> Share {
+            const unsigned long long m_a = __ballot(b.en_a != b.st_a);
+            const unsigned long long m_b = b_valid ? __ballot(b.en_b != b.st_b) : 0ull;
+            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)b.st_a, 0);
+            const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane((int)(b_valid ? b.en_b : b.en_a), 63);
+            const uint32_t nb = b1 - b0;
+            // the first run that starts at or behind x: its first triplet and its rank among the block's runs
+            auto first_run = [&](uint32_t x, uint32_t &start, uint32_t &rank) {
+                const unsigned long long c_a = __ballot(b.en_a != b.st_a && b.st_a >= x);
+                const unsigned long long c_b = b_valid ? __ballot(b.en_b != b.st_b && b.st_b >= x) : 0ull;
+                if (c_a) {
+                    const int i = __builtin_ctzll(c_a);
+                    start = (uint32_t)__builtin_amdgcn_readlane((int)b.st_a, i);
+                    rank = (uint32_t)__popcll(m_a & ((1ull << i) - 1ull));
+                } else if (c_b) {
+                    const int i = __builtin_ctzll(c_b);
+                    start = (uint32_t)__builtin_amdgcn_readlane((int)b.st_b, i);
+                    rank = (uint32_t)__popcll(m_a) + (uint32_t)__popcll(m_b & ((1ull << i) - 1ull));
+                } else {
+                    start = b1;
+                    rank = 0u;
+                }
+            };
+            Share sh;
+            uint32_t stop, stop_rank;
+            first_run(b0 + ((nb * (uint32_t)p) >> 2), sh.first, sh.rank);
+            if (p + 1 < PC_PROD) first_run(b0 + ((nb * (uint32_t)(p + 1)) >> 2), stop, stop_rank);
+            else stop = b1;
+            sh.first = __builtin_amdgcn_readfirstlane(sh.first);
+            sh.rank = __builtin_amdgcn_readfirstlane(sh.rank);
+            sh.n = __builtin_amdgcn_readfirstlane(stop) - sh.first;
+            return sh;
         };
         // gather words of triplets first + lane (clamped to the list)
         auto load_gather = [&](uint32_t first) -> uint32_t {
@@ -164,66 +198,70 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         };
         v2u xq[PC_SLOTS];
         // rows of triplets [base, base + 32) of a 64-triplet window whose gather words are gv; n = triplets left from
-        // base.  Rows past the end of the list are not requested (whole groups of eight) or read as zeros.
+        // base.  Whole groups of PC_STEP are requested; the rows behind the share's end inside the last group repeat a
+        // row of the share (their sums go to a scratch row).  A row's offset travels in a scalar register, so a
+        // request is two instructions: lane j's offset to the scalar file, then the load of 8 bytes per lane.
         auto issue_rows = [&](uint32_t gv, int half, uint32_t n) {
-            const uint32_t offv = ((uint32_t)(lane & 31) < n && (lane >> 5) == half) ? (gv & GATHER_INDEX) * ROWB : OOB_OFFSET;
+            const uint32_t src = (uint32_t)(lane & 31) < n ? gv : (uint32_t)__builtin_amdgcn_readlane((int)gv, 32 * half);
+            const uint32_t offv = (src & GATHER_INDEX) * ROWB;
 #pragma unroll
-            for (int j = 0; j < PC_SLOTS; ++j) {
-                if ((j & 7) == 0 && (uint32_t)j >= n) break;                                       // wave-uniform
-                const uint32_t off = (uint32_t)__builtin_amdgcn_readlane((int)offv, 32 * half + j);   // uniform
-                xq[j] = __builtin_amdgcn_raw_buffer_load_b64(frs, (int)(off + (uint32_t)lane * 8u), 0, 0);
+            for (int j0 = 0; j0 < PC_SLOTS; j0 += PC_STEP) {
+                if ((uint32_t)j0 >= n) break;                                                     // wave-uniform
+                uint32_t off[PC_STEP];
+#pragma unroll
+                for (int j = 0; j < PC_STEP; ++j) off[j] = (uint32_t)__builtin_amdgcn_readlane((int)offv, 32 * half + j0 + j);
+#pragma unroll
+                for (int j = 0; j < PC_STEP; ++j)
+                    xq[j0 + j] = __builtin_amdgcn_raw_buffer_load_b64(frs, (int)((uint32_t)lane * 8u), (int)off[j], 0);
             }
         };
 
         if (n_act > 0) {
-            uint32_t st_c, en_c, st_n, en_n, st_nn, en_nn;
-            load_bounds(0, st_c, en_c);
-            load_bounds(1, st_n, en_n);
-            load_bounds(2, st_nn, en_nn);
-            uint32_t s0_c = __builtin_amdgcn_readfirstlane(st_c);
-            uint32_t n_c = pvalid ? (uint32_t)__builtin_amdgcn_readlane((int)en_c, 31) - s0_c : 0u;
-            uint32_t gv_c = load_gather(s0_c);
-            uint32_t s0_n = __builtin_amdgcn_readfirstlane(st_n);
-            uint32_t gv_n = load_gather(s0_n);
-            issue_rows(gv_c, 0, n_c);
+            Bounds bd_c = load_bounds(0), bd_n = load_bounds(1), bd_nn = load_bounds(2);
+            Share sh_c = share_of(bd_c);
+            uint32_t gv_c = load_gather(sh_c.first);
+            Share sh_n = share_of(bd_n);
+            if (n_act < 2) sh_n.n = 0u;
+            uint32_t gv_n = load_gather(sh_n.first);
+            issue_rows(gv_c, 0, sh_c.n);
 
+            uint32_t dirty0 = ~0u, dirty1 = ~0u;           // per LDS tile: rows of this producer's centres that are not zeros
             for (int s = 0; s < n_act; ++s) {
-                // bounds three cells ahead, gather words two cells ahead
-                uint32_t st_3, en_3;
-                load_bounds(s + 3, st_3, en_3);
-                const uint32_t s0_nn = __builtin_amdgcn_readfirstlane(st_nn);
-                const uint32_t gv_nn = load_gather(s0_nn);
-
                 // ---- sums of this cell's runs -> S[s & 1] ------------------------------------------------
                 // Straight-line code per row (a taken branch costs a wave more than the dozen instructions it would
                 // skip): every row is added to the four fp32 sums of its lane (lane <-> channels 4 lane .. 4 lane + 3;
                 // v_dot2c_f32_bf16 would halve the instructions but runs at a quarter of the rate), the sums so far are
-                // rounded to bf16 and stored to the
-                // S row of the run's centre -- the store of the run's last row is the one that stays -- and the sums are
-                // cleared behind a run's last row.
-                const uint32_t hm = __builtin_amdgcn_readfirstlane(pvalid ? (uint32_t)(__ballot(en_c != st_c) & 0xffffffffull) : 0u);
-                if (lane == 0) hasrun[(s & 1) * 4 + p] = hm;
-                {   // rows of zeros for the centres without a run inside a group of 16 that has one: lane (c, half)
-                    // clears half a row
-                    const uint32_t z = ~hm & (((hm & 0xffffu) ? 0xffffu : 0u) | ((hm >> 16) ? 0xffff0000u : 0u));
+                // rounded to bf16 and stored to the S row of the run's centre -- the store of the run's last row is the
+                // one that stays -- and the row behind a run's last one starts new sums (one fused multiply-add per
+                // channel does both; a non-finite sum therefore spoils the later runs of this producer in the cell,
+                // all of them rows of this block's centres).
+                const unsigned long long m_a = __ballot(bd_c.en_a != bd_c.st_a);
+                const unsigned long long m_b = b_valid ? __ballot(bd_c.en_b != bd_c.st_b) : 0ull;
+                {   // rows of zeros for the centres 32 p .. 32 p + 31 without a run in this cell, unless the row is still
+                    // zero from the tile's last use two cells ago: lane (c, half) clears half a row
+                    const uint32_t has = (uint32_t)((p < 2 ? m_a : m_b) >> (32 * (p & 1)));
+                    const uint32_t z = ~has & ((s & 1) ? dirty1 : dirty0);
+                    if (s & 1) dirty1 = has; else dirty0 = has;
                     if ((z >> (lane & 31)) & 1u) {
                         char *zp = S + (size_t)(s & 1) * SBUF + (size_t)(32 * p + (lane & 31)) * SROW + (lane >> 5) * 256;
 #pragma unroll
                         for (int e = 0; e < 16; ++e) *reinterpret_cast<v4u *>(zp + 16 * e) = v4u{0u, 0u, 0u, 0u};
                     }
                 }
-                // the centres with a run, by rank: the run that ends r-th belongs to centre tab[r]
-                uint32_t *tab = rank_tab + p * 32;
-                if (lane < 32 && ((hm >> lane) & 1u)) tab[__popc(hm & ((1u << lane) - 1u))] = (uint32_t)lane;
+                // the block's centres with a run, by rank: the run that ends r-th belongs to centre tab[r]
+                uint32_t *tab = rank_tab + p * PC_ROWS;
+                if ((m_a >> lane) & 1ull) tab[__popcll(m_a & below)] = (uint32_t)lane;
+                if ((m_b >> lane) & 1ull) tab[__popcll(m_a) + __popcll(m_b & below)] = (uint32_t)(TILE + lane);
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
-                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-                uint32_t ends_before = 0u;                 // runs that ended in earlier passes
+                const uint32_t n_c = sh_c.n;
+                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, keep = 0.f;
+                uint32_t ends_before = sh_c.rank;          // runs that ended before the rows of this pass
                 uint32_t gv_w = gv_c;                      // gather words of the current 64-triplet window
                 for (uint32_t base = 0; base < n_c; base += PC_SLOTS) {
                     const int half = (int)((base >> 5) & 1u);
                     if (base != 0) {                       // later passes are not prefetched
-                        if (half == 0) gv_w = load_gather(s0_c + base);
+                        if (half == 0) gv_w = load_gather(sh_c.first + base);
                         issue_rows(gv_w, half, n_c - base);
                     }
                     const uint32_t left = n_c - base < PC_SLOTS ? n_c - base : PC_SLOTS;
@@ -231,37 +269,46 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                                                            (uint32_t)(lane & 31) < left);
                     const uint32_t flags = __builtin_amdgcn_readfirstlane((uint32_t)(fl >> (32 * half)));   // bit j: a run ends at row j
                     // lane j: where row j's sums go (byte offset of its centre's S row in the block's LDS; rows past the
-                    // end of the list, which are zeros, go to a scratch row)
+                    // end of the share, which are zeros, go to a scratch row)
                     const uint32_t rk = ends_before + (uint32_t)__popc(flags & ((1u << (lane & 31)) - 1u));
-                    const uint32_t ctr = tab[rk < 32u ? rk : 31u] & 31u;
-                    const uint32_t dsto = (uint32_t)(lane & 31) < left ? (uint32_t)(s & 1) * SBUF + (32u * p + ctr) * SROW
+                    const uint32_t ctr = tab[rk < (uint32_t)PC_ROWS ? rk : (uint32_t)PC_ROWS - 1u] & (uint32_t)(PC_ROWS - 1);
+                    const uint32_t dsto = (uint32_t)(lane & 31) < left ? (uint32_t)(s & 1) * SBUF + ctr * SROW
                                                                        : DUMMY_OFF + (uint32_t)p * ROWB;
                     ends_before += (uint32_t)__popc(flags);
 #pragma unroll
-                    for (int j = 0; j < PC_SLOTS; ++j) {
-                        if ((j & 7) == 0 && (uint32_t)j >= left) break;            // wave-uniform
-                        const v2u v = xq[j];
-                        a0 += __uint_as_float(v[0] << 16);
-                        a1 += __uint_as_float(v[0] & 0xffff0000u);
-                        a2 += __uint_as_float(v[1] << 16);
-                        a3 += __uint_as_float(v[1] & 0xffff0000u);
-                        const uint32_t off = (uint32_t)__builtin_amdgcn_readlane((int)dsto, j);
-                        *reinterpret_cast<v2u *>(lds + off + lane * 8) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
-                        // all-ones while the run goes on, zero behind its last row (wave-uniform, a scalar)
-                        const uint32_t keep = ((flags >> j) & 1u) - 1u;
-                        a0 = __uint_as_float(__float_as_uint(a0) & keep);
-                        a1 = __uint_as_float(__float_as_uint(a1) & keep);
-                        a2 = __uint_as_float(__float_as_uint(a2) & keep);
-                        a3 = __uint_as_float(__float_as_uint(a3) & keep);
+                    for (int j0 = 0; j0 < PC_SLOTS; j0 += PC_STEP) {
+                        if ((uint32_t)j0 >= left) break;                           // wave-uniform
+                        uint32_t at[PC_STEP];                                      // where the lane's 8 bytes of row j go
+#pragma unroll
+                        for (int j = 0; j < PC_STEP; ++j) at[j] = (uint32_t)__builtin_amdgcn_readlane((int)dsto, j0 + j) + (uint32_t)lane * 8u;
+#pragma unroll
+                        for (int j = 0; j < PC_STEP; ++j) asm volatile("" : "+v"(at[j]));   // all here, off the sums' critical path
+#pragma unroll
+                        for (int j = 0; j < PC_STEP; ++j) {
+                            const v2u v = xq[j0 + j];
+                            // sums = sums * keep + row: keep is 1 inside a run and 0 for the row behind a run's last one
+                            a0 = __builtin_fmaf(a0, keep, __uint_as_float(v[0] << 16));
+                            a1 = __builtin_fmaf(a1, keep, __uint_as_float(v[0] & 0xffff0000u));
+                            a2 = __builtin_fmaf(a2, keep, __uint_as_float(v[1] << 16));
+                            a3 = __builtin_fmaf(a3, keep, __uint_as_float(v[1] & 0xffff0000u));
+                            *reinterpret_cast<v2u *>(lds + at[j]) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
+                            keep = __uint_as_float((((flags >> (j0 + j)) & 1u) ^ 1u) * 0x3f800000u);   // wave-uniform, a scalar
+                        }
                     }
                 }
-                // ---- rows of the next cell ------------------------------------------------------------
-                const uint32_t n_n = (pvalid && s + 1 < n_act) ? (uint32_t)__builtin_amdgcn_readlane((int)en_n, 31) - s0_n : 0u;
-                issue_rows(gv_n, 0, n_n);
+                // ---- bounds three cells ahead, share and gather words two cells ahead, rows of the next cell --------
+                // (Behind the sums on purpose: the waits for rows that the compiler places between them are sized for
+                // the path on which the rows were requested a moment ago, and a load requested in front of the sums
+                // would be waited for there at its full latency, every cell.)
+                const Bounds bd_3 = load_bounds(s + 3);
+                Share sh_nn = share_of(bd_nn);
+                if (s + 2 >= n_act) sh_nn.n = 0u;
+                const uint32_t gv_nn = load_gather(sh_nn.first);
+                issue_rows(gv_n, 0, sh_n.n);
                 lds_barrier();
-                st_c = st_n; en_c = en_n; s0_c = s0_n; n_c = n_n; gv_c = gv_n;
-                st_n = st_nn; en_n = en_nn; s0_n = s0_nn; gv_n = gv_nn;
-                st_nn = st_3; en_nn = en_3;
+                bd_c = bd_n; sh_c = sh_n; gv_c = gv_n;
+                bd_n = bd_nn; sh_n = sh_nn; gv_n = gv_nn;
+                bd_nn = bd_3;
             }
         }
         lds_barrier();                                     // the consumers' last cell
@@ -276,9 +323,6 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     constexpr int NC32 = 2 * NCH;                          // 32-channel chunks of a source row
     constexpr size_t W_CELL = (size_t)PC_CONS * NC32 * 4 * 64;
     static_assert(NC32 % 4 == 0, "the ring of four chunks must close over a cell");
-    // s_waitcnt immediate: [3:0] and [15:14] vector-memory count, [6:4] export count, [11:8] LDS / scalar count.
-    // All vector-memory loads but the twelve newest done.
-    constexpr int WAIT_W = 0x0F7C;
     const v4u *wq = static_cast<const v4u *>(w_) + (size_t)q * NC32 * 4 * 64 + lane;     // + k * W_CELL
     v4f acc[PC_GROUPS][4];
 #pragma unroll
@@ -294,62 +338,36 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     }
     lds_barrier();                                         // iteration 0: the producers fill the first tile
     const uint32_t a_lane = (uint32_t)m * SROW + (uint32_t)g4 * 16u;
+    constexpr int GROW = 16 * (int)SROW;
     for (int s = 0; s < n_act; ++s) {
         const char *Sb = S + (size_t)(s & 1) * SBUF + a_lane;
-        const uint32_t h0 = hasrun[(s & 1) * 4 + 0], h1 = hasrun[(s & 1) * 4 + 1], h2 = hasrun[(s & 1) * 4 + 2],
-                       h3 = hasrun[(s & 1) * 4 + 3];
-        // groups of 16 centres with a run in this cell
-        uint32_t ag = 0;
-        ag |= (h0 & 0xffffu) ? 1u : 0u;  ag |= (h0 >> 16) ? 2u : 0u;
-        ag |= (h1 & 0xffffu) ? 4u : 0u;  ag |= (h1 >> 16) ? 8u : 0u;
-        ag |= (h2 & 0xffffu) ? 16u : 0u; ag |= (h2 >> 16) ? 32u : 0u;
-        ag |= (h3 & 0xffffu) ? 64u : 0u; ag |= (h3 >> 16) ? 128u : 0u;
-        ag = __builtin_amdgcn_readfirstlane(ag);
         const v4u *w_this = wq + (size_t)act[s] * W_CELL;
         const v4u *w_next = wq + (size_t)act[s + 1 < n_act ? s + 1 : s] * W_CELL;
-        // The work of a cell is a sequence of units (chunk ch, active group g), ch-major, four MFMAs each.  Every
-        // group keeps one A piece in registers; a unit requests the group's piece of the next chunk right after its
-        // MFMAs, so the piece a unit needs is always the oldest read in flight and n_ag - 1 newer ones follow it.
-        const int n_ag = __builtin_popcount(ag);
-        const uint32_t sb_addr = (uint32_t)(uintptr_t)(Sb - lds);       // the dynamic LDS block starts at address 0 (no static LDS)
+        // The work of a cell is 64 units (chunk ch, group g of 16 centres), ch-major, four MFMAs each, in one
+        // straight line: every group keeps one A piece in registers and requests its piece of the next chunk right
+        // after its MFMAs, eight units before it is needed, and every wait is a count known at compile time.  Groups
+        // without a triplet in the cell are multiplied all the same (their rows of S are zeros): testing a group's
+        // bit costs a wave more than the 64 cycles of the matrix pipe it would save, and a branch per unit leaves
+        // the compiler no static schedule.
         v4u piece[PC_GROUPS];
-        constexpr int GROW = 16 * (int)SROW;
-#define PCPP_PC_FIRST(g) if ((ag >> g) & 1u) lds_read_piece<g * GROW>(piece[g], sb_addr);
-        PCPP_PC_FIRST(0) PCPP_PC_FIRST(1) PCPP_PC_FIRST(2) PCPP_PC_FIRST(3)
-        PCPP_PC_FIRST(4) PCPP_PC_FIRST(5) PCPP_PC_FIRST(6) PCPP_PC_FIRST(7)
-#undef PCPP_PC_FIRST
-        auto chunk = [&](auto ch_tag) {
-            constexpr int ch = decltype(ch_tag)::value;
-            // W three chunks ahead (the next cell's first chunks after the last ones of this cell), then wait for this
-            // chunk's W pieces: all loads but the twelve newest
+#pragma unroll
+        for (int g = 0; g < PC_GROUPS; ++g) piece[g] = *reinterpret_cast<const v4u *>(Sb + g * GROW);
+#pragma unroll
+        for (int ch = 0; ch < NC32; ++ch) {
+            // W three chunks ahead (the next cell's first chunks after the last ones of this cell)
             {
-                constexpr int pre = (ch + 3) % NC32;       // chunk to request: of this cell, or of the next one
+                const int pre = (ch + 3) % NC32;
                 const v4u *src = (ch + 3 < NC32 ? w_this : w_next) + (size_t)pre * 4 * 64;
 #pragma unroll
                 for (int cg = 0; cg < 4; ++cg) wb[(ch + 3) & 3][cg] = src[cg * 64];
             }
-            __builtin_amdgcn_s_waitcnt(WAIT_W);
-            if (n_ag < 3) lds_wait<0>();                   // wave-uniform
-            auto unit = [&](auto g_tag) {
-                constexpr int g = decltype(g_tag)::value;
-                uint32_t on = (ag >> g) & 1u;
-                asm volatile("" : "+s"(on));               // a scalar, tested by a scalar branch
-                if (!on) return;
-                lds_wait<2>();
+#pragma unroll
+            for (int g = 0; g < PC_GROUPS; ++g) {
 #pragma unroll
                 for (int cg = 0; cg < 4; ++cg) mfma_16x16x32_acc(acc[g][cg], piece[g], wb[ch & 3][cg]);
-                if constexpr (ch + 1 < NC32) lds_read_piece<g * GROW + (ch + 1) * 64>(piece[g], sb_addr);
-            };
-            unit(std::integral_constant<int, 0>{}); unit(std::integral_constant<int, 1>{});
-            unit(std::integral_constant<int, 2>{}); unit(std::integral_constant<int, 3>{});
-            unit(std::integral_constant<int, 4>{}); unit(std::integral_constant<int, 5>{});
-            unit(std::integral_constant<int, 6>{}); unit(std::integral_constant<int, 7>{});
-        };
-        static_assert(NC32 == 8 && PC_GROUPS == 8, "the chunk and unit sequences are written out for eight of each");
-        chunk(std::integral_constant<int, 0>{}); chunk(std::integral_constant<int, 1>{});
-        chunk(std::integral_constant<int, 2>{}); chunk(std::integral_constant<int, 3>{});
-        chunk(std::integral_constant<int, 4>{}); chunk(std::integral_constant<int, 5>{});
-        chunk(std::integral_constant<int, 6>{}); chunk(std::integral_constant<int, 7>{});
+                if (ch + 1 < NC32) piece[g] = *reinterpret_cast<const v4u *>(Sb + g * GROW + (ch + 1) * 64);
+            }
+        }
         lds_barrier();
     }
     // the matrix cores' last results must have landed before ordinary instructions read the accumulators (the
@@ -398,7 +416,8 @@ int mvmr_rows_pc(const MvmrArgs &a, hipStream_t stream)
     constexpr int NCH = 4;
     const int64_t n_blocks = ceil_div(a.n_centres, PC_ROWS);
     const int64_t grid = ceil_div(n_blocks, NUM_XCD) * NUM_XCD;
-    const size_t lds = (size_t)2 * PC_ROWS * (64 * NCH * 2 + 16) + (8 + PC_PROD * 32) * sizeof(uint32_t) + (MAX_K + 1) * sizeof(int) + 12 + PC_PROD * 64 * NCH * 2;
+    const size_t lds = (size_t)2 * PC_ROWS * (64 * NCH * 2 + 16) + PC_PROD * PC_ROWS * sizeof(uint32_t) +
+                       (MAX_K + 1) * sizeof(int) + 12 + PC_PROD * 64 * NCH * 2;
     const uint32_t last = (uint32_t)(a.n_triplets - 1);
     const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * a.c_src * 2);
     if (a.out_dtype == PCPP_F32) {
