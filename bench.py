@@ -260,6 +260,15 @@ def measure_scene(scene_id: int, order: str, steps: int, warmup: int, spatial: b
         "roofline_per_op": per_op,
     }
 
+    if "bwd_input" in ops:
+        # what the library's own tuner (Sec. 3.3.2, closing remark) measures for this cloud and layer: one pass of
+        # fwd + bwd_input in either plan order; outside every timed region
+        del buffers
+        tuned, ms_a, ms_b = pcpp.pcpp_tune_plan_order(in_xyz, out_xyz, s.radius, s.t, n_t, s.c_in, s.c_out, fdt)
+        rec["plan_order_tuner"] = {"fwd_plus_bwd_input_ms_index_order": round(ms_a, 4),
+                                   "fwd_plus_bwd_input_ms_spatial_order": round(ms_b, 4),
+                                   "choice": "spatial" if tuned & pcpp.PLAN_SPATIAL else "index order"}
+
     if cpu_pair_tests > 0:
         import oracle
         # bounded sample of the same workload: the first n_sample outputs against all inputs

@@ -232,6 +232,29 @@ PCPP_API int pcpp_mvmr_fwd_static(const void *x, const void *w, void *out, int i
                                   const int64_t *seg_offsets, int64_t n_triplets,
                                   const void *plan, size_t plan_bytes, int plan_flags, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Choice of the processing order by measurement.  Sec. 3.3.2 ends with the remark that for configurations outside
+ * its analysis the order in which the triplets are processed can be selected by auto-tuning before the massive
+ * executions.  Here the public arrays are always in (k, o, i) order; what can differ is which centres share a tile
+ * of the plan: index order, or positions along a Z-order curve (PCPP_PLAN_SPATIAL).  The call builds both plans for
+ * this cloud, times pcpp_mvmr_fwd (and pcpp_mvmr_bwd_input when ops holds PCPP_PLAN_BWD_INPUT) on zero-filled
+ * features of this layer shape, three passes each after a warm-up, and reports
+ *   best_plan_flags  HOST int: ops, with PCPP_PLAN_SPATIAL added when that order was faster
+ *   ms_index_order, ms_spatial_order  HOST float, optional: the time of one pass in either order
+ * n_triplets must be |T| of this cloud (from a counting call of pcpp_build_triplets); build_flags is 0 or
+ * PCPP_BUILD_VOXEL; ops is PCPP_PLAN_FWD or PCPP_PLAN_FWD | PCPP_PLAN_BWD_INPUT.  workspace:
+ * pcpp_tune_workspace_bytes(...) bytes (device, 256-byte aligned; room for the triplets, the larger plan, the build's
+ * workspace and the layer's tensors).  The call waits for its result and creates two events for the timing; it is
+ * meant to run once per layer configuration, not per step.
+ * Errors: INVALID_ARG, WORKSPACE, and whatever the calls it makes return.
+ * ------------------------------------------------------------------------------------------- */
+PCPP_API size_t pcpp_tune_workspace_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int c_in, int c_out,
+                                          int in_dtype, int ops);
+PCPP_API int pcpp_tune_plan_order(const float *in_xyz, int64_t n_in, const float *out_xyz, int64_t n_out, float radius,
+                                  int t, int build_flags, int64_t n_triplets, int c_in, int c_out, int in_dtype, int ops,
+                                  void *workspace, size_t workspace_bytes, int *best_plan_flags, float *ms_index_order,
+                                  float *ms_spatial_order, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

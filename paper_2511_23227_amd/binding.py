@@ -72,6 +72,11 @@ def library() -> ctypes.CDLL:
     L.pcpp_mvmr_bwd_input.argtypes = [vp, vp, vp, i32, i32] + tail
     L.pcpp_mvmr_bwd_weight.restype = i32
     L.pcpp_mvmr_bwd_weight.argtypes = [vp, vp, vp, i32] + tail
+    L.pcpp_tune_workspace_bytes.restype = sz
+    L.pcpp_tune_workspace_bytes.argtypes = [i64, i64, i32, i64, i32, i32, i32, i32]
+    L.pcpp_tune_plan_order.restype = i32
+    L.pcpp_tune_plan_order.argtypes = [vp, i64, vp, i64, f32, i32, i32, i64, i32, i32, i32, i32, vp, sz,
+                                       ctypes.POINTER(i32), ctypes.POINTER(f32), ctypes.POINTER(f32), vp]
     L.pcpp_static_scratch_bytes.restype = sz
     L.pcpp_static_scratch_bytes.argtypes = []
     L.pcpp_mvmr_fwd_static.restype = i32
@@ -234,6 +239,23 @@ def pcpp_voxel_subsample(xyz: torch.Tensor, pitch: float) -> torch.Tensor:
                                   ctypes.cast(cnt.data_ptr(), ctypes.POINTER(ctypes.c_int64)), _ptr(ws), ws.numel(),
                                   _stream()))
     return kept[:int(cnt[0])]
+
+
+def pcpp_tune_plan_order(in_xyz: torch.Tensor, out_xyz: torch.Tensor, radius: float, t: int, n_triplets: int,
+                         c_in: int, c_out: int, dtype: torch.dtype, ops: int = PLAN_FWD | PLAN_BWD_INPUT,
+                         build_flags: int = 0) -> tuple[int, float, float]:
+    """The plan order (Sec. 3.3.2, closing remark on auto-tuning) that runs this layer faster on this cloud:
+    returns (plan flags to build with, ms per pass in index order, ms per pass in spatial order)."""
+    L = library()
+    assert in_xyz.is_cuda and in_xyz.is_contiguous() and out_xyz.is_contiguous() and in_xyz.dtype == torch.float32
+    n_in, n_out = int(in_xyz.shape[0]), int(out_xyz.shape[0])
+    code = 1 if dtype == torch.bfloat16 else 0
+    ws = _bytes(L.pcpp_tune_workspace_bytes(n_in, n_out, t, n_triplets, c_in, c_out, code, ops), in_xyz.device)
+    best, ms_a, ms_b = ctypes.c_int32(0), ctypes.c_float(0), ctypes.c_float(0)
+    _check(L.pcpp_tune_plan_order(_ptr(in_xyz), n_in, _ptr(out_xyz), n_out, float(radius), t, build_flags, n_triplets,
+                                  c_in, c_out, code, ops, _ptr(ws), ws.numel(), ctypes.byref(best), ctypes.byref(ms_a),
+                                  ctypes.byref(ms_b), _stream()))
+    return int(best.value), float(ms_a.value), float(ms_b.value)
 
 
 def _plan_args(T: Triplets):

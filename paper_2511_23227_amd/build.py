@@ -26,6 +26,7 @@ SOURCES = {
     # MFMA results in ordinary vector registers unless register pressure moves them (see the file header)
     "mvmr_rows_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "mvmr_rows_pc.hip": [],
+    "tune.hip": [],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-function",

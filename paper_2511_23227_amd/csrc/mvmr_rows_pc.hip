@@ -104,6 +104,7 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
     char *S = lds;                                                 // [2][PC_ROWS][SROW]
     uint32_t *rank_tab = reinterpret_cast<uint32_t *>(lds + 2 * SBUF);   // [PC_PROD][PC_ROWS]: per producer, the block's centres with a run, in order
     int *act = reinterpret_cast<int *>(rank_tab + PC_PROD * PC_ROWS);   // active cells, act[MAX_K] = their number
+    uint32_t *qmask = reinterpret_cast<uint32_t *>(act + MAX_K + 1);    // [2]: per LDS tile, bit q = centres 32 q .. 32 q + 31 hold a run
     constexpr uint32_t DUMMY_OFF = 2 * SBUF + PC_PROD * PC_ROWS * 4 + (MAX_K + 1) * 4 + 12;   // [PC_PROD][ROWB]: where rows
     static_assert(DUMMY_OFF % 16 == 0, "alignment of the scratch rows");                       // past a list's end are stored
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -248,6 +249,9 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                         for (int e = 0; e < 16; ++e) *reinterpret_cast<v4u *>(zp + 16 * e) = v4u{0u, 0u, 0u, 0u};
                     }
                 }
+                if (p == 0 && lane == 0)
+                    qmask[s & 1] = ((uint32_t)m_a != 0u) | (((uint32_t)(m_a >> 32) != 0u) << 1) |
+                                   (((uint32_t)m_b != 0u) << 2) | (((uint32_t)(m_b >> 32) != 0u) << 3);
                 // the block's centres with a run, by rank: the run that ends r-th belongs to centre tab[r]
                 uint32_t *tab = rank_tab + p * PC_ROWS;
                 if ((m_a >> lane) & 1ull) tab[__popcll(m_a & below)] = (uint32_t)lane;
@@ -343,31 +347,43 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         const char *Sb = S + (size_t)(s & 1) * SBUF + a_lane;
         const v4u *w_this = wq + (size_t)act[s] * W_CELL;
         const v4u *w_next = wq + (size_t)act[s + 1 < n_act ? s + 1 : s] * W_CELL;
-        // The work of a cell is 64 units (chunk ch, group g of 16 centres), ch-major, four MFMAs each, in one
-        // straight line: every group keeps one A piece in registers and requests its piece of the next chunk right
-        // after its MFMAs, eight units before it is needed, and every wait is a count known at compile time.  Groups
-        // without a triplet in the cell are multiplied all the same (their rows of S are zeros): testing a group's
-        // bit costs a wave more than the 64 cycles of the matrix pipe it would save, and a branch per unit leaves
-        // the compiler no static schedule.
-        v4u piece[PC_GROUPS];
+        // The work of a cell is 64 units (chunk ch, group g of 16 centres), ch-major, four MFMAs each.  Every group
+        // keeps one A piece in registers and requests its piece of the next chunk right after its MFMAs.  When all
+        // four quarters of the block (32 centres each) hold a triplet in the cell -- half of the cells, and the ones
+        // with most rows -- the 256 MFMAs run in one straight line with every wait a count known at compile time;
+        // groups without a triplet are multiplied all the same (their rows of S are zeros).  Otherwise one test per
+        // chunk and quarter skips the quarters without a triplet: those are the cells with few rows, where the
+        // producers are quick and the consumers set the pace.
+        const uint32_t qm = __builtin_amdgcn_readfirstlane(qmask[s & 1]);
+        auto cell = [&](auto dense_c) {
+            constexpr bool DENSE = decltype(dense_c)::value;
+            v4u piece[PC_GROUPS];
 #pragma unroll
-        for (int g = 0; g < PC_GROUPS; ++g) piece[g] = *reinterpret_cast<const v4u *>(Sb + g * GROW);
+            for (int g = 0; g < PC_GROUPS; ++g)
+                if (DENSE || ((qm >> (g >> 1)) & 1u)) piece[g] = *reinterpret_cast<const v4u *>(Sb + g * GROW);
 #pragma unroll
-        for (int ch = 0; ch < NC32; ++ch) {
-            // W three chunks ahead (the next cell's first chunks after the last ones of this cell)
-            {
-                const int pre = (ch + 3) % NC32;
-                const v4u *src = (ch + 3 < NC32 ? w_this : w_next) + (size_t)pre * 4 * 64;
+            for (int ch = 0; ch < NC32; ++ch) {
+                // W three chunks ahead (the next cell's first chunks after the last ones of this cell)
+                {
+                    const int pre = (ch + 3) % NC32;
+                    const v4u *src = (ch + 3 < NC32 ? w_this : w_next) + (size_t)pre * 4 * 64;
 #pragma unroll
-                for (int cg = 0; cg < 4; ++cg) wb[(ch + 3) & 3][cg] = src[cg * 64];
+                    for (int cg = 0; cg < 4; ++cg) wb[(ch + 3) & 3][cg] = src[cg * 64];
+                }
+#pragma unroll
+                for (int qd = 0; qd < PC_GROUPS / 2; ++qd) {
+                    if (DENSE || ((qm >> qd) & 1u)) {
+#pragma unroll
+                        for (int g = 2 * qd; g < 2 * qd + 2; ++g) {
+#pragma unroll
+                            for (int cg = 0; cg < 4; ++cg) mfma_16x16x32_acc(acc[g][cg], piece[g], wb[ch & 3][cg]);
+                            if (ch + 1 < NC32) piece[g] = *reinterpret_cast<const v4u *>(Sb + g * GROW + (ch + 1) * 64);
+                        }
+                    }
+                }
             }
-#pragma unroll
-            for (int g = 0; g < PC_GROUPS; ++g) {
-#pragma unroll
-                for (int cg = 0; cg < 4; ++cg) mfma_16x16x32_acc(acc[g][cg], piece[g], wb[ch & 3][cg]);
-                if (ch + 1 < NC32) piece[g] = *reinterpret_cast<const v4u *>(Sb + g * GROW + (ch + 1) * 64);
-            }
-        }
+        };
+        cell(std::false_type{});
         lds_barrier();
     }
     // the matrix cores' last results must have landed before ordinary instructions read the accumulators (the

@@ -37,25 +37,28 @@ __global__ void so_init(int *mins)
     if (threadIdx.x < 3) mins[threadIdx.x] = INT_MAX;
 }
 
+// Lowest grid coordinate per axis.  so_coord never decreases with the coordinate, so the minimum is taken over the
+// floats and converted once per block; one atomic per block and axis.
 __global__ __launch_bounds__(SO_THREADS) void so_min(const float *__restrict__ xyz, int64_t n, double inv_pitch,
                                                      int *__restrict__ mins)
 {
-    int m[3] = {INT_MAX, INT_MAX, INT_MAX};
+    __shared__ float part[SO_WAVES][3];
+    float m[3] = {INFINITY, INFINITY, INFINITY};
     const int64_t stride = (int64_t)gridDim.x * SO_THREADS;
     for (int64_t p = (int64_t)blockIdx.x * SO_THREADS + threadIdx.x; p < n; p += stride)
 #pragma unroll
-        for (int a = 0; a < 3; ++a) {
-            const int c = so_coord(xyz[3 * p + a], inv_pitch);
-            m[a] = c < m[a] ? c : m[a];
-        }
+        for (int a = 0; a < 3; ++a) m[a] = fminf(m[a], xyz[3 * p + a]);     // a NaN is passed over
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            const int o = __shfl_xor(m[a], d, 64);
-            m[a] = o < m[a] ? o : m[a];
-        }
-        if ((threadIdx.x & 63) == 0) atomicMin(&mins[a], m[a]);
+        for (int d = 32; d >= 1; d >>= 1) m[a] = fminf(m[a], __shfl_xor(m[a], d, 64));
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6][a] = m[a];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        float v = part[0][threadIdx.x];
+        for (int w = 1; w < SO_WAVES; ++w) v = fminf(v, part[w][threadIdx.x]);
+        atomicMin(&mins[threadIdx.x], so_coord(v, inv_pitch));
     }
 }
 
@@ -204,7 +207,7 @@ int spatial_order(const float *xyz, int64_t n, double pitch, int32_t *perm, void
     uint32_t *table = reinterpret_cast<uint32_t *>(ws + s.table_off);
     const double inv_pitch = 1.0 / pitch;
     int64_t rb = ceil_div(n, SO_THREADS);
-    if (rb > 1024) rb = 1024;
+    if (rb > 512) rb = 512;
     so_init<<<1, 64, 0, stream>>>(mins);
     so_min<<<(unsigned)rb, SO_THREADS, 0, stream>>>(xyz, n, inv_pitch, mins);
     so_keys<<<(unsigned)ceil_div(n, SO_THREADS), SO_THREADS, 0, stream>>>(xyz, n, inv_pitch, mins, keys[0], vals[0]);

@@ -143,3 +143,40 @@ def test_non_finite_source_row_stays_local(pcpp, c, dt):
     groups = np.unique(linked // 128)
     far = ~np.isin(np.arange(n) // 128, groups)
     assert np.isfinite(out[far]).all()
+
+
+@pytest.mark.parametrize("c, dt, voxel", [(32, torch.float32, False), (256, torch.bfloat16, False), (64, torch.bfloat16, True)])
+def test_tune_plan_order(pcpp, c, dt, voxel):
+    """The tuner of the plan's order (Sec. 3.3.2, closing remark): it reports positive times for both orders, returns
+    flags that differ from the request by PCPP_PLAN_SPATIAL at most and match the faster time, leaves nothing behind
+    that a later build depends on, and the plan built with its answer gives the oracle's result."""
+    rng = np.random.default_rng(77)
+    n, t = 6000, 3
+    r = 0.08 if not voxel else 0.05
+    p = rng.uniform(0, 1, (n, 3)).astype(np.float32)
+    K = t ** 3
+    d = dev(p)
+    bflags = pcpp.BUILD_VOXEL if voxel else 0
+    n_t = pcpp.pcpp_build_triplets(d, d, r, t, plan_flags=pcpp.PLAN_FWD | bflags).n_triplets
+    ops = pcpp.PLAN_FWD | pcpp.PLAN_BWD_INPUT
+    best, ms_index, ms_spatial = pcpp.pcpp_tune_plan_order(d, d, r, t, n_t, c, c, dt, ops, bflags)
+    assert ms_index > 0 and ms_spatial > 0
+    assert best & ~pcpp.PLAN_SPATIAL == ops
+    assert bool(best & pcpp.PLAN_SPATIAL) == (ms_spatial < ms_index)
+    with pytest.raises(pcpp.PcppError):
+        pcpp.pcpp_tune_plan_order(d, d, r, t, n_t + 1, c, c, dt, ops, bflags)        # not this cloud's |T|
+    with pytest.raises(pcpp.PcppError):
+        pcpp.pcpp_tune_plan_order(d, d, r, t, n_t, c, c, dt, pcpp.PLAN_BWD_INPUT, bflags)   # forward side missing
+    T = pcpp.pcpp_build_triplets(d, d, r, t, plan_flags=best | bflags)
+    if voxel:
+        o, i, k, seg = oracle.build_triplets_general(p, p, np.float32(r), t, mode=oracle.MODE_VOXEL)
+    else:
+        o, i, k, seg = oracle.build_triplets(p, p, np.float32(r), t)
+    assert T.n_triplets == n_t == len(o)
+    x = rng.standard_normal((n, c)).astype(np.float32)
+    w = (rng.standard_normal((K, c, c)) / np.sqrt(K * c)).astype(np.float32)
+    name = "f32"
+    if dt == torch.bfloat16:
+        x, w, name = scenes.round_to_bf16(x), scenes.round_to_bf16(w), "bf16"
+    ref, scale = oracle_fwd(x, w, o, i, k, n)
+    assert_close(pcpp.pcpp_mvmr_fwd(dev(x, dt), dev(w, dt), T).cpu().numpy(), ref, scale, TOL[name], "fwd on the tuned plan")
