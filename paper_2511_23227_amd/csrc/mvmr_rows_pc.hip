@@ -9,18 +9,20 @@
 //       load instruction, lane <-> four channels -- add them up in fp32 on the vector ALUs, round each run's sum to
 //       bf16 once and store it as row `centre` of an LDS tile S[128][C_src]; centres without a run get rows of zeros;
 //   consumer waves (four, one per SIMD; each owns 64 destination channels of all 128 centres, 128 accumulator
-//       registers) multiply the whole tile by their slice of W[k] on the matrix cores, acc += S . W[k]^T, 256 MFMAs
-//       in one straight line.  Groups of 16 centres without a triplet in the cell are multiplied too: on this
-//       workload 5.4 of 8 groups have one, but a test-and-branch per group costs a wave more than the 64 cycles of
-//       the matrix pipe that it saves and leaves no static schedule.
+//       registers) multiply the tile by their slice of W[k] on the matrix cores, acc += S . W[k]^T, chunk of 32
+//       source channels by chunk; per chunk, one test per quarter of the block (32 centres) skips the quarters
+//       that hold no triplet in the cell (3.0 of 4 do on this workload; within a quarter the rows of centres
+//       without a run are zeros and are multiplied all the same).  A test per group of 16 centres was slower: it
+//       costs the in-order wave about as much as the 64 cycles of the matrix pipe that it saves.
 // The two run one cell apart on two LDS tiles, one barrier per cell: while the matrix cores work on cell j the
 // rows of cell j + 1 are in flight.  A consumer's W slice (64 x C_src of the 16.4 MB at K = 125) comes straight from
 // memory / L2 into registers in fragment order, three 32-channel chunks ahead of its use (a ring of four); nothing
 // but S goes through LDS.  Every destination row is accumulated in registers across all cells and written once by
 // its owner: no atomics, fixed summation order.
 //
-// What bounds it: the matrix pipe needs 256 x 16 = 4096 cycles per cell; the consumer's loads of W and of S add
-// about 1500 (each is an instruction of the same in-order wave).  A producer spends about 70 cycles per row when
+// What bounds it: the matrix pipe needs 256 x 16 = 4096 cycles for a cell in which every quarter holds a triplet;
+// the consumer's loads of W and of S add about 1500 (each is an instruction of the same in-order wave), and in a
+// cell with few rows the 32 loads of its W slice, three chunks ahead, are what it waits for.  A producer spends about 70 cycles per row when
 // alone on its SIMD (10 vector instructions for the sums, two conversions, and a 512-byte LDS store that costs
 // 24) and about 105 beside a wave that issues MFMAs back to back, since both issue through the SIMD's vector
 // port; with the per-cell bookkeeping a producer's cell takes about as long as a consumer's.
