@@ -222,10 +222,10 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         if (n_act > 0) {
             Bounds bd_c = load_bounds(0), bd_n = load_bounds(1), bd_nn = load_bounds(2);
             Share sh_c = share_of(bd_c);
-            uint32_t gv_c = load_gather(sh_c.first);
+            uint32_t gv_c = load_gather(sh_c.first), gx_c = load_gather(sh_c.first + 64u);   // first and second window
             Share sh_n = share_of(bd_n);
             if (n_act < 2) sh_n.n = 0u;
-            uint32_t gv_n = load_gather(sh_n.first);
+            uint32_t gv_n = load_gather(sh_n.first), gx_n = load_gather(sh_n.first + 64u);
             issue_rows(gv_c, 0, sh_c.n);
 
             uint32_t dirty0 = ~0u, dirty1 = ~0u;           // per LDS tile: rows of this producer's centres that are not zeros
@@ -263,13 +263,24 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                 const uint32_t n_c = sh_c.n;
                 float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, keep = 0.f;
                 uint32_t ends_before = sh_c.rank;          // runs that ended before the rows of this pass
-                uint32_t gv_w = gv_c;                      // gather words of the current 64-triplet window
+                // Rows travel in passes of 32 through the 32 row registers.  The first pass of a cell was requested
+                // during the previous cell; every later pass is requested group by group during the pass before it, each
+                // group into the registers that the current pass has just added up, so that shares of more than 32
+                // rows (a third of the cells, and the ones that set the pace) do not wait out a memory round trip.
+                uint32_t gv_w = gv_c, gv_x = gx_c;         // gather words of the current 64-triplet window and of the next
                 for (uint32_t base = 0; base < n_c; base += PC_SLOTS) {
                     const int half = (int)((base >> 5) & 1u);
-                    if (base != 0) {                       // later passes are not prefetched
-                        if (half == 0) gv_w = load_gather(sh_c.first + base);
-                        issue_rows(gv_w, half, n_c - base);
+                    if (base != 0 && half == 0) {          // next window; the one behind it is needed a pass from now
+                        gv_w = gv_x;
+                        gv_x = load_gather(sh_c.first + base + 64u);
                     }
+                    // the next pass: its triplets sit in the other half of this window or in the first half of the next
+                    const uint32_t n_next = n_c - base > PC_SLOTS ? n_c - base - PC_SLOTS : 0u;
+                    const int nhalf = half ^ 1;
+                    const uint32_t g_next = half == 0 ? gv_w : gv_x;
+                    const uint32_t src_next = (uint32_t)(lane & 31) < n_next ? g_next
+                                                                             : (uint32_t)__builtin_amdgcn_readlane((int)g_next, 32 * nhalf);
+                    const uint32_t off_next = (src_next & GATHER_INDEX) * ROWB;     // lane 32 nhalf + j: row j of the next pass
                     const uint32_t left = n_c - base < PC_SLOTS ? n_c - base : PC_SLOTS;
                     const unsigned long long fl = __ballot((gv_w & GATHER_LAST) != 0u && (lane >> 5) == half &&
                                                            (uint32_t)(lane & 31) < left);
@@ -300,6 +311,14 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                             *reinterpret_cast<v2u *>(lds + at[j]) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
                             keep = __uint_as_float((((flags >> (j0 + j)) & 1u) ^ 1u) * 0x3f800000u);   // wave-uniform, a scalar
                         }
+                        if ((uint32_t)j0 < n_next) {                               // wave-uniform
+                            uint32_t off[PC_STEP];
+#pragma unroll
+                            for (int j = 0; j < PC_STEP; ++j) off[j] = (uint32_t)__builtin_amdgcn_readlane((int)off_next, 32 * nhalf + j0 + j);
+#pragma unroll
+                            for (int j = 0; j < PC_STEP; ++j)
+                                xq[j0 + j] = __builtin_amdgcn_raw_buffer_load_b64(frs, (int)((uint32_t)lane * 8u), (int)off[j], 0);
+                        }
                     }
                 }
                 // ---- bounds three cells ahead, share and gather words two cells ahead, rows of the next cell --------
@@ -309,11 +328,11 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                 const Bounds bd_3 = load_bounds(s + 3);
                 Share sh_nn = share_of(bd_nn);
                 if (s + 2 >= n_act) sh_nn.n = 0u;
-                const uint32_t gv_nn = load_gather(sh_nn.first);
+                const uint32_t gv_nn = load_gather(sh_nn.first), gx_nn = load_gather(sh_nn.first + 64u);
                 issue_rows(gv_n, 0, sh_n.n);
                 lds_barrier();
-                bd_c = bd_n; sh_c = sh_n; gv_c = gv_n;
-                bd_n = bd_nn; sh_n = sh_nn; gv_n = gv_nn;
+                bd_c = bd_n; sh_c = sh_n; gv_c = gv_n; gx_c = gx_n;
+                bd_n = bd_nn; sh_n = sh_nn; gv_n = gv_nn; gx_n = gx_nn;
                 bd_nn = bd_3;
             }
         }
@@ -349,13 +368,12 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
         const char *Sb = S + (size_t)(s & 1) * SBUF + a_lane;
         const v4u *w_this = wq + (size_t)act[s] * W_CELL;
         const v4u *w_next = wq + (size_t)act[s + 1 < n_act ? s + 1 : s] * W_CELL;
-        // The work of a cell is 64 units (chunk ch, group g of 16 centres), ch-major, four MFMAs each.  Every group
-        // keeps one A piece in registers and requests its piece of the next chunk right after its MFMAs.  When all
-        // four quarters of the block (32 centres each) hold a triplet in the cell -- half of the cells, and the ones
-        // with most rows -- the 256 MFMAs run in one straight line with every wait a count known at compile time;
-        // groups without a triplet are multiplied all the same (their rows of S are zeros).  Otherwise one test per
-        // chunk and quarter skips the quarters without a triplet: those are the cells with few rows, where the
-        // producers are quick and the consumers set the pace.
+        // The work of a cell is up to 64 units (chunk ch, group g of 16 centres), ch-major, four MFMAs each.  Every
+        // group keeps one A piece in registers and requests its piece of the next chunk right after its MFMAs.  One
+        // test per chunk and quarter of the block (32 centres) skips the quarters without a triplet in the cell: those
+        // are the cells with few rows, where the producers are quick and the consumers set the pace.  (A second,
+        // branch-free copy of the loop for the cells in which all four quarters hold a triplet made the register
+        // allocator spill the accumulators.)
         const uint32_t qm = __builtin_amdgcn_readfirstlane(qmask[s & 1]);
         auto cell = [&](auto dense_c) {
             constexpr bool DENSE = decltype(dense_c)::value;
