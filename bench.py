@@ -87,7 +87,7 @@ def compulsory_bytes(op: str, n_t: int, n_in: int, n_out: int, c_in: int, c_out:
 
 
 def measure_scene(scene_id: int, order: str, steps: int, warmup: int, spatial: bool, cpu_pair_tests: float,
-                  traffic: dict, cold: bool):
+                  traffic: dict, cold: bool, tuner: bool = True):
     """All figures of one scene.  Returns the record."""
     import numpy as np
     import torch
@@ -260,7 +260,7 @@ def measure_scene(scene_id: int, order: str, steps: int, warmup: int, spatial: b
         "roofline_per_op": per_op,
     }
 
-    if "bwd_input" in ops:
+    if "bwd_input" in ops and tuner:
         # what the library's own tuner (Sec. 3.3.2, closing remark) measures for this cloud and layer: one pass of
         # fwd + bwd_input in either plan order; outside every timed region
         del buffers
@@ -303,6 +303,7 @@ def main() -> int:
     ap.add_argument("--only", action="store_true", help="measure the headline scene only (profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the library-kernel peak measurements")
+    ap.add_argument("--no-tuner", action="store_true", help="skip the plan-order tuner's record (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 256 MiB device-to-device copy (the kernel of known size against which the "
                          "FETCH_SIZE / WRITE_SIZE counters are scaled) and exit")
@@ -337,7 +338,7 @@ def main() -> int:
 
     cpu_tests = 0.0 if args.no_cpu_baseline else 1.0e10      # pair tests of the brute-force search per scene (~10 s)
     head = measure_scene(args.scene, args.order, args.steps, args.warmup, want_spatial(args.scene), 2.5 * cpu_tests,
-                         traffic, cold=True)
+                         traffic, cold=True, tuner=not args.no_tuner)
     others = {}
     if not args.only:
         for sid, order in ((1, "default"), (2, "default"), (3, "default"), (4, "default"), (2, "morton"), (5, "morton")):
@@ -345,7 +346,7 @@ def main() -> int:
                 continue
             print(f"bench.py: scene {sid} ({order})", file=sys.stderr, flush=True)
             r = measure_scene(sid, order, args.steps, args.warmup, want_spatial(sid),
-                              cpu_tests if order == "default" else 0.0, traffic, cold=False)
+                              cpu_tests if order == "default" else 0.0, traffic, cold=False, tuner=not args.no_tuner)
             others[f"{r['config']['workload']}" + ("" if order == "default" else "_" + order)] = r
 
     peaks = None
@@ -411,8 +412,9 @@ def main() -> int:
         "roofline_per_op": head["roofline_per_op"],
         "scenes": others,
     }
-    if "cpu_baseline" in head:
-        result["cpu_baseline"] = head["cpu_baseline"]
+    for key in ("cpu_baseline", "plan_order_tuner"):
+        if key in head:
+            result[key] = head[key]
     print(json.dumps(result))
     return 0
 
