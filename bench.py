@@ -57,6 +57,23 @@ def load_measured_traffic() -> dict:
     return table
 
 
+def load_measured_mfma() -> dict:
+    """MFMA instructions per launch (SQ_INSTS_MFMA) from the counter summaries under profiles/: lines
+    `COUNTERS scene=5 order=default op=fwd kernel=.. src=file.hip:hash insts_mfma=..`, used only while the named
+    source file still has that hash."""
+    table = {}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_counters.txt"))):
+        for line in open(path):
+            if not line.startswith("COUNTERS "):
+                continue
+            kv = dict(item.split("=", 1) for item in line.split()[1:])
+            src, _, digest = kv.get("src", ":").partition(":")
+            if source_hash(src) == digest:
+                table[(int(kv["scene"]), kv["order"], kv["op"])] = {"insts_mfma": int(kv["insts_mfma"]),
+                                                                    "file": os.path.relpath(path, ROOT)}
+    return table
+
+
 def algorithmic_bytes(op: str, n_t: int, n_in: int, n_out: int, c_in: int, c_out: int, K: int, s_in: int,
                       s_out: int, n_pairs: int | None = None) -> float:
     """Bytes the method itself has to move per launch (Eq. (3) of Sec. 3.3.2 with W read once):
@@ -219,6 +236,14 @@ def measure_scene(scene_id: int, order: str, steps: int, warmup: int, spatial: b
             tf = nominal / (ms * 1e-3) / 1e12
             rec.update({"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
                         "frac": round(tf / MFMA_PEAK_TFLOPS["bf16"], 4)})
+            cm = load_measured_mfma().get((scene_id, order, "fwd" if op == "bwd_input" else op))
+            if cm:
+                # what the kernel issues, counted by the hardware: includes the rows of zeros that ride along in a
+                # group of centres, so it is context, never the graded fraction
+                issued = cm["insts_mfma"] * 2.0 * 16 * 16 * 32
+                rec["issued_tflop_incl_zero_rows"] = round(issued / 1e12, 3)
+                rec["issued_tflops_incl_zero_rows"] = round(issued / (ms * 1e-3) / 1e12, 1)
+                rec["issued_source"] = cm["file"]
             pairs = {"fwd": n_pairs_o, "bwd_input": n_pairs_i}.get(op)
             if pairs:
                 # after the run sums one product with W[k] per distinct (cell, centre) pair is the least the matrix
