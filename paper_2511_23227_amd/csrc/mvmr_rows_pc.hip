@@ -266,27 +266,28 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                 // Rows travel in passes of 32 through the 32 row registers.  The first pass of a cell was requested
                 // during the previous cell; every later pass is requested group by group during the pass before it, each
                 // group into the registers that the current pass has just added up, so that shares of more than 32
-                // rows (a third of the cells, and the ones that set the pace) do not wait out a memory round trip.
-                uint32_t gv_w = gv_c, gv_x = gx_c;         // gather words of the current 64-triplet window and of the next
-                for (uint32_t base = 0; base < n_c; base += PC_SLOTS) {
-                    const int half = (int)((base >> 5) & 1u);
-                    if (base != 0 && half == 0) {          // next window; the one behind it is needed a pass from now
-                        gv_w = gv_x;
-                        gv_x = load_gather(sh_c.first + base + 64u);
-                    }
-                    // the next pass: its triplets sit in the other half of this window or in the first half of the next
-                    const uint32_t n_next = n_c - base > PC_SLOTS ? n_c - base - PC_SLOTS : 0u;
+                // rows (a third of the cells, and the ones that set the pace) do not wait out a memory round trip.  A
+                // pass that refills always requests all eight groups, and the passes of a share are written out one
+                // behind the other without a loop: the number of row loads younger than the one a group needs is
+                // then a constant that the compiler can see (28 while refilling, fewer in a share's last pass), and
+                // it waits for exactly that.  The gather words of the first 128 triplets of a share are prefetched;
+                // beyond that (rare) the passes are requested one at a time.
+                // pass over `left` (<= 32) rows whose gather words are half `half` of gv_w; when REFILL, the n_next rows of
+                // the pass behind it (gather words: the other half, of g_next) are requested on the way
+                auto pass = [&](int half, uint32_t left, uint32_t gv_w, uint32_t g_next, uint32_t n_next, auto refill_c) {
+                    constexpr bool REFILL = decltype(refill_c)::value;
                     const int nhalf = half ^ 1;
-                    const uint32_t g_next = half == 0 ? gv_w : gv_x;
-                    const uint32_t src_next = (uint32_t)(lane & 31) < n_next ? g_next
-                                                                             : (uint32_t)__builtin_amdgcn_readlane((int)g_next, 32 * nhalf);
-                    const uint32_t off_next = (src_next & GATHER_INDEX) * ROWB;     // lane 32 nhalf + j: row j of the next pass
-                    const uint32_t left = n_c - base < PC_SLOTS ? n_c - base : PC_SLOTS;
+                    uint32_t off_next = 0u;                // lane 32 nhalf + j: row j of the next pass
+                    if (REFILL) {
+                        const uint32_t src_next = (uint32_t)(lane & 31) < n_next ? g_next
+                                                                                 : (uint32_t)__builtin_amdgcn_readlane((int)g_next, 32 * nhalf);
+                        off_next = (src_next & GATHER_INDEX) * ROWB;
+                    }
                     const unsigned long long fl = __ballot((gv_w & GATHER_LAST) != 0u && (lane >> 5) == half &&
                                                            (uint32_t)(lane & 31) < left);
                     const uint32_t flags = __builtin_amdgcn_readfirstlane((uint32_t)(fl >> (32 * half)));   // bit j: a run ends at row j
                     // lane j: where row j's sums go (byte offset of its centre's S row in the block's LDS; rows past the
-                    // end of the share, which are zeros, go to a scratch row)
+                    // end of the share go to a scratch row)
                     const uint32_t rk = ends_before + (uint32_t)__popc(flags & ((1u << (lane & 31)) - 1u));
                     const uint32_t ctr = tab[rk < (uint32_t)PC_ROWS ? rk : (uint32_t)PC_ROWS - 1u] & (uint32_t)(PC_ROWS - 1);
                     const uint32_t dsto = (uint32_t)(lane & 31) < left ? (uint32_t)(s & 1) * SBUF + ctr * SROW
@@ -294,7 +295,7 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                     ends_before += (uint32_t)__popc(flags);
 #pragma unroll
                     for (int j0 = 0; j0 < PC_SLOTS; j0 += PC_STEP) {
-                        if ((uint32_t)j0 >= left) break;                           // wave-uniform
+                        if (!REFILL && (uint32_t)j0 >= left) break;                // wave-uniform
                         uint32_t at[PC_STEP];                                      // where the lane's 8 bytes of row j go
 #pragma unroll
                         for (int j = 0; j < PC_STEP; ++j) at[j] = (uint32_t)__builtin_amdgcn_readlane((int)dsto, j0 + j) + (uint32_t)lane * 8u;
@@ -311,7 +312,7 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                             *reinterpret_cast<v2u *>(lds + at[j]) = v2u{cvt_pk_bf16(a0, a1), cvt_pk_bf16(a2, a3)};
                             keep = __uint_as_float((((flags >> (j0 + j)) & 1u) ^ 1u) * 0x3f800000u);   // wave-uniform, a scalar
                         }
-                        if ((uint32_t)j0 < n_next) {                               // wave-uniform
+                        if (REFILL) {
                             uint32_t off[PC_STEP];
 #pragma unroll
                             for (int j = 0; j < PC_STEP; ++j) off[j] = (uint32_t)__builtin_amdgcn_readlane((int)off_next, 32 * nhalf + j0 + j);
@@ -320,6 +321,32 @@ __global__ __launch_bounds__(PC_THREADS) void rows_pc_kernel(const void *__restr
                                 xq[j0 + j] = __builtin_amdgcn_raw_buffer_load_b64(frs, (int)((uint32_t)lane * 8u), (int)off[j], 0);
                         }
                     }
+                };
+                constexpr uint32_t PREFETCHED = 4u * PC_SLOTS;      // triplets whose gather words gv_c and gx_c hold
+                const uint32_t n_main = n_c < PREFETCHED ? n_c : PREFETCHED;
+                const std::true_type yes{};
+                const std::false_type no{};
+                if (n_main > PC_SLOTS) {
+                    pass(0, PC_SLOTS, gv_c, gv_c, n_main - PC_SLOTS, yes);
+                    if (n_main > 2u * PC_SLOTS) {
+                        pass(1, PC_SLOTS, gv_c, gx_c, n_main - 2u * PC_SLOTS, yes);
+                        if (n_main > 3u * PC_SLOTS) {
+                            pass(0, PC_SLOTS, gx_c, gx_c, n_main - 3u * PC_SLOTS, yes);
+                            pass(1, n_main - 3u * PC_SLOTS, gx_c, gx_c, 0u, no);
+                        } else {
+                            pass(0, n_main - 2u * PC_SLOTS, gx_c, gx_c, 0u, no);
+                        }
+                    } else {
+                        pass(1, n_main - PC_SLOTS, gv_c, gx_c, 0u, no);
+                    }
+                } else if (n_main > 0u) {
+                    pass(0, n_main, gv_c, gv_c, 0u, no);
+                }
+                for (uint32_t base = PREFETCHED; base < n_c; base += PC_SLOTS) {      // rare: one pass at a time
+                    const uint32_t gv_t = load_gather(sh_c.first + base);
+                    const uint32_t left = n_c - base < PC_SLOTS ? n_c - base : PC_SLOTS;
+                    issue_rows(gv_t, 0, left);
+                    pass(0, left, gv_t, gv_t, 0u, no);
                 }
                 // ---- bounds three cells ahead, share and gather words two cells ahead, rows of the next cell --------
                 // (Behind the sums on purpose: the waits for rows that the compiler places between them are sized for
