@@ -316,6 +316,84 @@ def measure_scene(scene_id: int, order: str, steps: int, warmup: int, spatial: b
     return rec
 
 
+def measure_variants(steps: int, warmup: int) -> dict:
+    """The steps either side of the path (Sec. 4.1) and the degraded operator (Sec. 3.2, "Ours (degraded)" of Sec. 4.2) on
+    the benchmark clouds: voxel-grid down-sampling, a batch of clouds built in one call, the voxel operator on the
+    strided scene beside the ball operator."""
+    import numpy as np
+    import torch
+
+    import paper_2511_23227_amd as pcpp
+    import scenes
+
+    def timed(fn, reps):
+        for _ in range(warmup):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    out = {}
+    # (1) voxel-grid down-sampling (lowest index per voxel, original coordinates kept)
+    for sid, pitch in ((4, 0.0415), (5, 0.2)):
+        s = scenes.make_scene(sid)
+        xyz = torch.from_numpy(s.in_xyz).cuda()
+        kept = pcpp.pcpp_voxel_subsample(xyz, pitch)
+        ms = timed(lambda: pcpp.pcpp_voxel_subsample(xyz, pitch), steps)
+        out[f"voxel_subsample_scene{sid}"] = {"n": s.n_in, "pitch": pitch, "n_kept": int(kept.numel()), "ms": round(ms, 4),
+                                              "points_per_s": round(s.n_in / (ms * 1e-3), 1),
+                                              "note": "includes the host's wait for the count"}
+    # (2) a batch of eight clouds (scene 2's cloud under eight rigid shifts) built in one call against eight single builds
+    s = scenes.make_scene(2)
+    nb = 8
+    shifts = np.arange(nb, dtype=np.float32)[:, None] * np.array([[0.25, 0.5, 0.125]], dtype=np.float32)
+    clouds = [s.in_xyz + shifts[b] for b in range(nb)]
+    cat = torch.from_numpy(np.ascontiguousarray(np.concatenate(clouds))).cuda()
+    offs = torch.arange(nb + 1, dtype=torch.int32, device="cuda") * s.n_in
+    flags = pcpp.PLAN_FWD | pcpp.PLAN_BWD_INPUT
+    Tb = pcpp.pcpp_build_triplets(cat, cat, s.radius, s.t, plan_flags=flags, in_offsets=offs, out_offsets=offs)
+    n_tb = Tb.n_triplets
+    ms_b = timed(lambda: pcpp.pcpp_build_triplets(cat, cat, s.radius, s.t, plan_flags=flags, in_offsets=offs, out_offsets=offs,
+                                                  capacity=n_tb), steps)
+    single = [torch.from_numpy(np.ascontiguousarray(c)).cuda() for c in clouds]
+    n_ts = pcpp.pcpp_build_triplets(single[0], single[0], s.radius, s.t, plan_flags=flags).n_triplets
+
+    def eight():
+        for c in single:
+            pcpp.pcpp_build_triplets(c, c, s.radius, s.t, plan_flags=flags, capacity=n_ts + 4096)
+    ms_s = timed(eight, max(2, steps // 2))
+    out["batched_build_8x_scene2"] = {"n_points": nb * s.n_in, "n_triplets": n_tb, "ms_one_batched_call": round(ms_b, 4),
+                                      "ms_eight_single_calls": round(ms_s, 4),
+                                      "build_pairs_per_s": round(n_tb / (ms_b * 1e-3), 1),
+                                      "note": "both allocate their outputs per call"}
+    del Tb, cat, single
+    # (3) the degraded (voxel) operator on the strided scene: pitch 2 r / t, so that the t^3 voxels span the ball's cube
+    s = scenes.make_scene(4)
+    x, w, dy = scenes.make_features(s)
+    bf = torch.bfloat16
+    xin, xout = torch.from_numpy(s.in_xyz).cuda(), torch.from_numpy(s.out_xyz).cuda()
+    dx_, dw_, ddy = (torch.from_numpy(a_).cuda().to(bf) for a_ in (x, w, dy))
+    rec = {}
+    for name, size, bflag in (("ball", s.radius, 0), ("voxel", 2.0 * s.radius / s.t, pcpp.BUILD_VOXEL)):
+        T = pcpp.pcpp_build_triplets(xin, xout, size, s.t, plan_flags=flags | bflag)
+        n_t = T.n_triplets
+        ms_build = timed(lambda: pcpp.pcpp_build_triplets(xin, xout, size, s.t, plan_flags=flags | bflag, capacity=n_t), steps)
+        ms_f = timed(lambda: pcpp.pcpp_mvmr_fwd(dx_, dw_, T), steps)
+        ms_i = timed(lambda: pcpp.pcpp_mvmr_bwd_input(ddy, dw_, T), steps)
+        ms_w = timed(lambda: pcpp.pcpp_mvmr_bwd_weight(dx_, ddy, T), steps)
+        rec[name] = {"size": round(float(size), 5), "n_triplets": n_t, "build_ms": round(ms_build, 4), "fwd_ms": round(ms_f, 4),
+                     "bwd_input_ms": round(ms_i, 4), "bwd_weight_ms": round(ms_w, 4),
+                     "pairs_per_s": round(n_t / ((ms_f + ms_i + ms_w) * 1e-3), 1)}
+    rec["note"] = "times include the allocation of the outputs by the binding"
+    out["degraded_operator_scene4"] = rec
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -329,6 +407,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the library-kernel peak measurements")
     ap.add_argument("--no-tuner", action="store_true", help="skip the plan-order tuner's record (profiling runs)")
+    ap.add_argument("--no-variants", action="store_true", help="skip the down-sampling / batch / voxel-operator records")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 256 MiB device-to-device copy (the kernel of known size against which the "
                          "FETCH_SIZE / WRITE_SIZE counters are scaled) and exit")
@@ -437,6 +516,9 @@ def main() -> int:
         "roofline_per_op": head["roofline_per_op"],
         "scenes": others,
     }
+    if not args.only and not args.no_variants:
+        print("bench.py: variants", file=sys.stderr, flush=True)
+        result["variants"] = measure_variants(args.steps, args.warmup)
     for key in ("cpu_baseline", "plan_order_tuner"):
         if key in head:
             result[key] = head[key]
