@@ -106,7 +106,11 @@ constexpr int rows_min_waves(bool bf16, int c_src, int c_dst)
     return (!bf16 && c_src == 32 && c_dst == 32) ? 4 : ((bf16 && c_src == 64 && c_dst == 64) ? 3 : ((bf16 && c_src == 64 && c_dst == 128) ? 2 : 1));
 }
 
-template <bool BF16, int C_SRC, int C_DST, int NW, typename TOut>
+// NWIN = windows of 64 triplets per (cell, block) whose gather indices are requested one cell ahead: 1, or 3 for clouds
+// with many neighbours per cell, where the rows of the second and third window would otherwise wait for an index
+// load on top of their own round trip.  (A variant of its own because the layers with few neighbours per cell sit at
+// a register-count step and lose a wave per SIMD, or spill, to the four registers that the indices take.)
+template <bool BF16, int C_SRC, int C_DST, int NW, int NWIN, typename TOut>
 __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void rows_kernel(const void *__restrict__ feat_, const void *__restrict__ w_,
                                                        TOut *__restrict__ dst, int64_t n_centres, int K,
                                                        const int32_t *__restrict__ gather, uint32_t last_triplet,
@@ -158,11 +162,16 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
     load_runs(wave, st_c, en_c);
     load_runs(wave + NW, st_n, en_n);
     uint32_t bs_c = __builtin_amdgcn_readlane(st_c, 0);
-    int32_t iv_c;
-    {
-        const uint32_t p = bs_c + lane;
-        iv_c = gather[p < last_triplet ? p : last_triplet];
-    }
+    // gather indices of the block's first, second and third 64 triplets in the cell (the later ones only when the
+    // cell has that many: a load that is not needed still costs the layers with few neighbours per cell)
+    int32_t iv_c, iw_c = 0, ix_c = 0;
+    auto load_indices = [&](uint32_t bs, uint32_t n_cell, int32_t &iv, int32_t &iw, int32_t &ix) {
+        const uint32_t p = bs + lane;
+        iv = gather[p < last_triplet ? p : last_triplet];
+        if (NWIN > 1 && n_cell > 64u) iw = gather[p + 64u < last_triplet ? p + 64u : last_triplet];      // wave-uniform
+        if (NWIN > 1 && n_cell > 128u) ix = gather[p + 128u < last_triplet ? p + 128u : last_triplet];
+    };
+    load_indices(bs_c, (uint32_t)__builtin_amdgcn_readlane(en_c, 31) - bs_c, iv_c, iw_c, ix_c);
     __syncthreads();                                 // selection table complete
 
     v16f acc[NB];
@@ -176,11 +185,8 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
         uint32_t st_nn, en_nn;
         load_runs(k + 2 * NW, st_nn, en_nn);
         const uint32_t bs_n = __builtin_amdgcn_readlane(st_n, 0);
-        int32_t iv_n;
-        {
-            const uint32_t p = bs_n + lane;
-            iv_n = gather[p < last_triplet ? p : last_triplet];
-        }
+        int32_t iv_n, iw_n = 0, ix_n = 0;
+        load_indices(bs_n, (uint32_t)__builtin_amdgcn_readlane(en_n, 31) - bs_n, iv_n, iw_n, ix_n);
         const uint32_t cn_c = en_c - st_c;
         const uint32_t n = __builtin_amdgcn_readlane(en_c, 31) - bs_c;   // triplets of the block in cell k
         if (n != 0) {                                                    // wave-uniform
@@ -201,7 +207,11 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
 #pragma unroll
                 for (int pc = 0; pc < NPC_EARLY; ++pc) bw[b][pc] = wk[(b * NPC + pc) * 64];
             for (uint32_t g0 = 0; g0 < n; g0 += 64) {
-                if (g0 != 0) {                       // source rows of the next 64 triplets
+                if (NWIN > 1 && g0 == 64) {          // the second and third 64 triplets: asked for one cell ahead, so that
+                    ivc = iw_c;                      // their rows do not wait for an index load on top of their own
+                } else if (NWIN > 1 && g0 == 128) {
+                    ivc = ix_c;
+                } else if (g0 != 0) {                // source rows of the next 64 triplets
                     const uint32_t p = bs_c + g0 + lane;
                     ivc = gather[p < last_triplet ? p : last_triplet];
                 }
@@ -340,7 +350,7 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
             }
         }
         // rotate the pipeline
-        st_c = st_n; en_c = en_n; bs_c = bs_n; iv_c = iv_n;
+        st_c = st_n; en_c = en_n; bs_c = bs_n; iv_c = iv_n; iw_c = iw_n; ix_c = ix_n;
         st_n = st_nn; en_n = en_nn;
     }
 
@@ -370,7 +380,7 @@ __global__ __launch_bounds__(NW * 64, rows_min_waves(BF16, C_SRC, C_DST)) void r
         }
 }
 
-template <bool BF16, int C_SRC, int C_DST, int NW>
+template <bool BF16, int C_SRC, int C_DST, int NW, int NWIN>
 int launch(const MvmrArgs &a, hipStream_t stream)
 {
     const int64_t blocks = ceil_div(a.n_centres, ROWS);
@@ -378,10 +388,10 @@ int launch(const MvmrArgs &a, hipStream_t stream)
     const uint32_t last = (uint32_t)(a.n_triplets - 1);
     const uint32_t feat_bytes = (uint32_t)((size_t)a.n_src * C_SRC * (BF16 ? 2 : 4));
     if (a.out_dtype == PCPP_F32) {
-        rows_kernel<BF16, C_SRC, C_DST, NW, float><<<(unsigned)blocks, NW * 64, lds, stream>>>(
+        rows_kernel<BF16, C_SRC, C_DST, NW, NWIN, float><<<(unsigned)blocks, NW * 64, lds, stream>>>(
             a.feat, a.w, static_cast<float *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
     } else {
-        rows_kernel<BF16, C_SRC, C_DST, NW, uint16_t><<<(unsigned)blocks, NW * 64, lds, stream>>>(
+        rows_kernel<BF16, C_SRC, C_DST, NW, NWIN, uint16_t><<<(unsigned)blocks, NW * 64, lds, stream>>>(
             a.feat, a.w, static_cast<uint16_t *>(a.dst), a.n_centres, a.K, a.gather, last, feat_bytes, a.side);
     }
     PCPP_HIP_CHECK(hipGetLastError());
@@ -395,8 +405,10 @@ int launch_k(const MvmrArgs &a, hipStream_t stream)
 {
     // (64 -> 128: one wave per block measured 10 % faster on the strided scene -- twice the blocks for a layer with
     // few output points, and no partial sums to add)
-    if constexpr (BF16 && C_SRC == 64 && C_DST == 128) return launch<BF16, C_SRC, C_DST, 1>(a, stream);
-    else return launch<BF16, C_SRC, C_DST, 2>(a, stream);
+    constexpr int NW = (BF16 && C_SRC == 64 && C_DST == 128) ? 1 : 2;
+    // more than 48 triplets per (cell, block of 32 centres) on average: index windows ahead
+    if (a.n_triplets * ROWS > 48 * a.n_centres * (int64_t)a.K) return launch<BF16, C_SRC, C_DST, NW, 3>(a, stream);
+    return launch<BF16, C_SRC, C_DST, NW, 1>(a, stream);
 }
 
 }  // namespace
