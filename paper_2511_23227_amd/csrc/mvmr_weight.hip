@@ -164,6 +164,14 @@ __global__ __launch_bounds__(WAVES * 64) void weight_f32_kernel(const float *__r
 
     v4f acc[QO][2][QI][2];
     bool first = true;
+    // o (lanes 0..31) and i (lanes 32..63) of the 32 triplets from `pos` on, clamped to the list
+    auto load_oi = [&](int64_t pos) -> int32_t {
+        int64_t t = pos + (lane & 31);
+        t = t < n_triplets ? t : n_triplets - 1;
+        return lane < 32 ? tri_o[t] : tri_i[t];
+    };
+    int64_t pf_pos = p;
+    int32_t oi_pf = load_oi(p);
     while (p < p_end) {
         int64_t q_end = seg[k + 1];
         if (q_end > p_end) q_end = p_end;
@@ -179,9 +187,12 @@ __global__ __launch_bounds__(WAVES * 64) void weight_f32_kernel(const float *__r
 
         for (int64_t b0 = p; b0 < q_end; b0 += 32) {
             const int n = (int)(q_end - b0 < 32 ? q_end - b0 : 32);
-            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
-            int32_t oi = 0;
-            if ((lane & 31) < n) oi = lane < 32 ? tri_o[b0 + lane] : tri_i[b0 + lane - 32];
+            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32: asked for one step
+            // ahead (the next step starts 32 triplets on, or where the next cell's run starts), so that a step's rows
+            // wait for one memory round trip, not for two in a row
+            const int32_t oi = pf_pos == b0 ? oi_pf : load_oi(b0);                 // wave-uniform
+            pf_pos = b0 + 32 < q_end ? b0 + 32 : q_end;
+            oi_pf = load_oi(pf_pos);
             v2f dyw[QO][8], xw[QI][8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -268,6 +279,14 @@ __global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__r
 
     v4f acc[QO][4][QI][4];
     bool first = true;
+    // o (lanes 0..31) and i (lanes 32..63) of the 32 triplets from `pos` on, clamped to the list
+    auto load_oi = [&](int64_t pos) -> int32_t {
+        int64_t t = pos + (lane & 31);
+        t = t < n_triplets ? t : n_triplets - 1;
+        return lane < 32 ? tri_o[t] : tri_i[t];
+    };
+    int64_t pf_pos = p;
+    int32_t oi_pf = load_oi(p);
     while (p < p_end) {
         int64_t q_end = seg[k + 1];
         if (q_end > p_end) q_end = p_end;
@@ -283,9 +302,12 @@ __global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__r
 
         for (int64_t b0 = p; b0 < q_end; b0 += 32) {
             const int n = (int)(q_end - b0 < 32 ? q_end - b0 : 32);
-            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32
-            int32_t oi = 0;
-            if ((lane & 31) < n) oi = lane < 32 ? tri_o[b0 + lane] : tri_i[b0 + lane - 32];
+            // lanes 0..31 hold o of triplet b0 + lane, lanes 32..63 hold i of triplet b0 + lane - 32: asked for one step
+            // ahead (the next step starts 32 triplets on, or where the next cell's run starts), so that a step's rows
+            // wait for one memory round trip, not for two in a row
+            const int32_t oi = pf_pos == b0 ? oi_pf : load_oi(b0);                 // wave-uniform
+            pf_pos = b0 + 32 < q_end ? b0 + 32 : q_end;
+            oi_pf = load_oi(pf_pos);
             v2u dyw[QO][8], xw[QI][8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
