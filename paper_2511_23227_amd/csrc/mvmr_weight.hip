@@ -370,25 +370,48 @@ __global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__r
 // ---------------------------------------------------------------------------------------------
 // bf16 256 -> 256: one block of eight waves per chunk, wave w owning the 128 x 64 sub-block (output channels
 // 128 (w / 4) .., input channels 64 (w % 4) ..) of dW[k].  With 128 accumulator registers a wave has no room
-// to keep a second batch of rows in flight, and two waves per SIMD hide little of a gather's latency.  Here
-// the block fetches every row of a batch of 32 triplets once (x[i] and dy[o]: 32 x 1 KB, 64 bytes per thread)
-// and passes it through LDS, so the rows are four batches deep in flight at a fixed cost of registers:
-//   step s:  request the indices of batch s + 4 | request the rows of batch s + 2 (indices asked for two steps
-//            ago) | multiply batch s out of LDS buffer s % 2 | store the rows of batch s + 1 (asked for one
-//            step ago) into buffer (s + 1) % 2 | barrier
-// A batch never crosses the end of a cell's run; rows past its end are stored as zeros.  The operands are read
-// from LDS in the layout weight_wide_kernel reads from memory.  Thread (row r = tid / 16, h = (tid / 8) % 2,
-// q = tid % 8) moves bytes 128 j + 16 q .. + 15 (j = 0..3) of x[i_r] (h = 0) or dy[o_r] (h = 1).
+// to keep rows in flight, and two waves per SIMD hide little of a gather's latency.  Here the block fetches every
+// row of a batch of 32 triplets once (x[i] and dy[o]: 32 x 1 KB) with loads that write straight into LDS
+// (global_load_lds_dwordx4: lane l of the wave writes bytes 16 l .. 16 l + 15 behind the address in M0, so one
+// instruction moves two rows), into a ring of four batch buffers: rows in flight cost no registers, and the
+// batches s + 1 .. s + 3 are on their way while batch s is multiplied.  The triplets' indices travel the same way
+// (global_load_lds_dword into a small ring per wave), two batches ahead of their rows.
+//   step s:  request the indices of batch s + 5 | first half of batch s (output channels co0 .. co0 + 63, operands
+//            read during step s - 1) with one request for rows of batch s + 3 behind every four MFMAs, the LDS
+//            reads for the second half under way | wait for the rows of batch s + 1, zero its dy rows past the
+//            batch's end | barrier | read the first operands of batch s + 1, second half of batch s meanwhile |
+//            wait for the indices of batch s + 4, read them into registers
+// The requests are spread between the MFMAs because a request can wait hundreds of cycles for room in the memory
+// pipeline and the wave issues in order: bunched at the head of the step they kept the matrix pipe idle (5.1 ->
+// 4.7 ms on a million-point cloud); with the operands of the next batch read during the second half, LDS reads and
+// MFMAs of the block's lock-stepped waves overlap.
+// Wave w moves rows 4 w .. 4 w + 3 of x and of dy.  The compiler does not see these loads, so the waits are written
+// by hand; they are exact because every step issues the same five memory instructions per wave, in the same order
+// (one for indices, four for rows; a batch that is short or empty re-reads its last triplet, or triplet 0): behind
+// the rows to wait for, ten younger instructions may still be outstanding, behind the indices nine.  (The partial
+// sums' stores and the rare reads of a cell's bounds, which the compiler does see, only make these waits stricter.)
+// A batch never crosses the end of a cell's run.  The operands are read from LDS in the layout weight_wide_kernel
+// reads from memory.
 // ---------------------------------------------------------------------------------------------
 constexpr int LDS_WAVES = 8;
-constexpr int LDS_BATCH_BYTES = 32 * 1024;        // 32 rows of x (512 B) then 32 rows of dy (512 B)
+constexpr int LDS_GROUP_PITCH = 8 * 512 + 128;    // eight rows of 512 B, then 128 B: the rows r, r + 8, r + 16, r + 24 that
+                                                  // one LDS read touches start in different banks
+constexpr int LDS_BATCH_BYTES = 8 * LDS_GROUP_PITCH;   // 32 rows of x (four groups) then 32 rows of dy
+constexpr int LDS_NBUF = 4;                        // batch buffers: batch s in s % 4
+constexpr int LDS_INDEX_BYTES = LDS_WAVES * LDS_NBUF * 256;   // per wave and batch: 64 words, word 4 a + r = index of
+                                                              // row 4 w + r in tri_i (a = 0) or tri_o (a = 1)
+constexpr int LDS_WEIGHT_BYTES = LDS_NBUF * LDS_BATCH_BYTES + LDS_INDEX_BYTES;
 
-struct Batch {
-    int64_t b0;     // first triplet
-    int n;          // triplets (0: no batch)
-    int k;          // cell
-    bool last;      // the run (or the chunk) ends with this batch
-};
+// 16 bytes per lane from `src` (per lane) to LDS byte address `lds` + 16 lane (`lds` wave-uniform)
+__device__ inline void load_to_lds_b128(const void *src, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds) : "memory");
+}
+// 4 bytes per lane to `lds` + 4 lane
+__device__ inline void load_to_lds_b32(const void *src, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds) : "memory");
+}
 
 __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uint16_t *__restrict__ x,
                                                                         const uint16_t *__restrict__ dy,
@@ -398,59 +421,65 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
                                                                         const int64_t *__restrict__ seg, int K,
                                                                         int64_t n_triplets, int chunk, int64_t n_chunks)
 {
-    constexpr int C = 256, ROW = C * 2, X_OFF = 0, DY_OFF = 32 * ROW;
-    extern __shared__ __attribute__((aligned(16))) unsigned char stage[];        // two batches
+    constexpr int C = 256, ROW = C * 2, GP = LDS_GROUP_PITCH, X_OFF = 0, DY_OFF = 4 * GP;   // row r: (r / 8) GP + (r % 8) ROW
+    extern __shared__ __attribute__((aligned(16))) unsigned char stage[];        // four batches, then the index rings
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int ci0 = (wave & 3) * 64, co0 = (wave >> 2) * 128;
     const int64_t chunk_id = blockIdx.x;
-    int64_t p = chunk_id * chunk;
-    int64_t p_end = p + chunk;
-    if (p_end > n_triplets) p_end = n_triplets;
+    const int64_t p0 = chunk_id * chunk;                                          // positions below are relative to it
+    const uint32_t q_end = (uint32_t)((p0 + chunk < n_triplets ? p0 + chunk : n_triplets) - p0);
 
-    // cell of the first triplet: the k with seg[k] <= p < seg[k+1]
+    // cell of the first triplet: the k with seg[k] <= p0 < seg[k+1]
     int k = 0;
     for (int kb = 0; kb < K; kb += 64) {
         const int kk = kb + lane;
-        const bool hit = kk < K && seg[kk] <= p && p < seg[kk + 1];
+        const bool hit = kk < K && seg[kk] <= p0 && p0 < seg[kk + 1];
         const unsigned long long msk = __ballot(hit);
         if (msk) { k = kb + __ffsll((long long)msk) - 1; break; }
     }
     k = __builtin_amdgcn_readfirstlane(k);
-    // run_end: end of cell k's run inside the chunk, read from seg only when the cell changes
-    int64_t run_end = seg[k + 1] < p_end ? seg[k + 1] : p_end;
-    auto next_batch = [&]() -> Batch {
-        while (p < p_end) {
-            if (run_end <= p) {                       // next cell (empty runs are passed over)
+    // A batch travels through the steps as one word: triplets | ends its run << 8 | cell << 16 (0: no batch).  run_end:
+    // end of cell k's run inside the chunk, read from seg only when the cell changes.
+    auto end_of = [&](int kk) -> uint32_t {
+        const int64_t e = seg[kk + 1] - p0;
+        return e < (int64_t)q_end ? (uint32_t)e : q_end;
+    };
+    uint32_t q = 0, run_end = end_of(k);
+    uint32_t q5 = 0;                              // first triplet of the batch that next_batch returned last
+    auto next_batch = [&]() -> uint32_t {
+        while (q < q_end) {
+            if (run_end <= q) {                       // next cell (empty runs are passed over)
                 ++k;
-                run_end = seg[k + 1] < p_end ? seg[k + 1] : p_end;
+                run_end = end_of(k);
                 continue;
             }
-            Batch b;
-            b.b0 = p;
-            b.n = (int)(run_end - p < 32 ? run_end - p : 32);
-            b.k = k;
-            p += b.n;
-            b.last = p == run_end;
-            return b;
+            const uint32_t n = run_end - q < 32u ? run_end - q : 32u;
+            q5 = q;
+            q += n;
+            return n | (q == run_end ? 256u : 0u) | ((uint32_t)k << 16);
         }
-        return Batch{0, 0, 0, false};
+        q5 = 0;
+        return 0u;
     };
 
-    // mover role of this thread
-    const int r = tid >> 4, h = (tid >> 3) & 1, q = tid & 7;
-    const int32_t *tri_mine = h ? tri_o : tri_i;
-    const unsigned char *rows_mine = reinterpret_cast<const unsigned char *>(h ? dy : x);
-    const int lds_mine = (h ? DY_OFF : X_OFF) + r * ROW + q * 16;
+    // mover role of this lane: rows 4 wave + 2 j + half (j = 0, 1), bytes 16 piece .. of the row
+    const int half = lane >> 5, piece = lane & 31;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)(stage);
+    const uint32_t ring0 = lds0 + LDS_NBUF * LDS_BATCH_BYTES + wave * (LDS_NBUF * 256);
+    const unsigned char *ring = stage + LDS_NBUF * LDS_BATCH_BYTES + wave * (LDS_NBUF * 256);
+    const unsigned char *xb = reinterpret_cast<const unsigned char *>(x) + piece * 16;
+    const unsigned char *dyb = reinterpret_cast<const unsigned char *>(dy) + piece * 16;
+    // index requests: lane -> (array, row lane % 4)
+    const int32_t *tri_lane = (((lane >> 2) & 1) ? tri_o : tri_i) + p0;
+    const int r_lane = 4 * wave + (lane & 3);
 
-    Batch b0 = Batch{0, 0, 0, false}, b1 = b0, b2 = b0, b3 = b0, b4 = next_batch();
-    // Registers that a load is still filling are never copied (a copy would wait for the load): the two sets
-    // of row registers and the two index registers swap roles from one step to the next instead, with the step
-    // written once for each parity.
-    int32_t idx[2] = {0, 0};                     // row index of this thread in batch s + 2 (then s + 4): idx[s % 2]
-    v4u rows[2][4];                              // this thread's 64 bytes of batch s + 2: rows[s % 2]; s + 1: the other
-#pragma unroll
-    for (int j = 0; j < 4; ++j) rows[0][j] = rows[1][j] = v4u{0u, 0u, 0u, 0u};
+    // the first steps request rows before any index has arrived: they read zeros (row 0) from the ring
+    *reinterpret_cast<v4u *>(stage + LDS_NBUF * LDS_BATCH_BYTES + wave * (LDS_NBUF * 256) + lane * 16) = v4u{0u, 0u, 0u, 0u};
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+
+    uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0, w4 = 0, w5 = next_batch();      // batches s .. s + 5
+    int cur = 0;                                  // buffer of batch s
 
     v4f acc[2][4][4];
 #pragma unroll
@@ -461,56 +490,95 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
             for (int d = 0; d < 4; ++d) acc[a][b][d] = v4f{0.f, 0.f, 0.f, 0.f};
     bool first = true;
 
-    auto step = [&](auto parity) __attribute__((always_inline)) {
-        constexpr int PAR = decltype(parity)::value;
-        // rows of batch s + 2 (index asked for two steps ago), then the index of batch s + 4 into the same register
-        // (both unconditional, so that the waits can be counted exactly: past a batch's end the index read is
-        // clamped to the last triplet and the row it names is fetched and then stored as zeros)
+    // operands of batch s that are read during step s - 1: the x side as MFMA operands, the dy rows of the first half
+    v4u bv[4];
+    v2u dyw0[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bv[e] = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dyw0[e] = v2u{0u, 0u};
+    int32_t ix[2] = {0, 0}, io[2] = {0, 0};     // rows 4 wave + 2 j + half of the batch whose rows are requested next
+    // acc[qo][qd] += dy(16 channels)^T . x over the batch's 32 triplets; dyw: this lane's words of the dy rows
+    auto multiply = [&](int qo, int qd, const v2u (&dyw)[8]) __attribute__((always_inline)) {
+        v4u av;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd)
+            av[wd] = __builtin_amdgcn_perm(dyw[2 * wd + 1][qd >> 1], dyw[2 * wd][qd >> 1],
+                                           (qd & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+        for (int qs = 0; qs < 4; ++qs)
+            acc[qo][qd][qs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv[qs]), acc[qo][qd][qs], 0, 0, 0);
+    };
+
+    // one step; COMPUTE = false for the five steps that fill the pipeline (no batch s yet).  Once a batch has reached
+    // the front, every step has one until the chunk is used up, and nothing is left behind the last one.
+    auto step = [&](auto compute) __attribute__((always_inline)) {
+        constexpr bool COMPUTE = decltype(compute)::value;
+        // indices of batch s + 5
         {
-            const unsigned char *src = rows_mine + (size_t)idx[PAR] * ROW + q * 16;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) rows[PAR][j] = *reinterpret_cast<const v4u *>(src + j * 128);
+            const int n5 = (int)(w5 & 255u);
+            int t = (int)q5 + (r_lane < n5 ? r_lane : n5 - 1);
+            if (t < 0) t = 0;
+            load_to_lds_b32(tri_lane + t, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring0 + ((cur + 5) & 3) * 256)));
         }
+        // rows of batch s + 3, one request behind every four MFMAs of the first half of batch s (output channels
+        // co0 .. co0 + 63; its operands were read one step ago): a request can wait long for room in the memory
+        // pipeline, and the matrix pipe should have work meanwhile.  The reads for the second half go first.
+        const unsigned char *buf = stage + cur * LDS_BATCH_BYTES;
+        v2u dyw1[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            dyw1[e] = *reinterpret_cast<const v2u *>(buf + DY_OFF + g * GP + e * ROW + (co0 + 64 + 4 * m) * 2);
         {
-            const int64_t t = b4.b0 + r;
-            idx[PAR] = tri_mine[t < n_triplets ? t : n_triplets - 1];
+            const uint32_t dst = lds0 + (uint32_t)((cur + 3) & 3) * LDS_BATCH_BYTES +
+                                 (uint32_t)((wave >> 1) * GP + 4 * (wave & 1) * ROW);
+            auto request = [&](int i) __attribute__((always_inline)) {
+                const int j = i >> 1;
+                if (i & 1)
+                    load_to_lds_b128(dyb + (size_t)io[j] * ROW,
+                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + DY_OFF + 2 * j * ROW)));
+                else
+                    load_to_lds_b128(xb + (size_t)ix[j] * ROW,
+                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + X_OFF + 2 * j * ROW)));
+            };
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                if constexpr (COMPUTE) multiply(0, qd, dyw0);
+                request(qd);
+            }
         }
-        // batch s out of LDS
-        if (b0.n) {
-            const unsigned char *buf = stage + PAR * LDS_BATCH_BYTES;
-            v2u xw[8];
+        // the rows of batch s + 1 have arrived; past its end the dy rows become zeros (the x rows there repeat the
+        // batch's last triplet)
+        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        {
+            const int n1 = (int)(w1 & 255u);
+            if (n1 > 0 && n1 < 32) {
+                unsigned char *dst = stage + ((cur + 1) & 3) * LDS_BATCH_BYTES + DY_OFF + piece * 16;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                xw[e] = *reinterpret_cast<const v2u *>(buf + X_OFF + (8 * g + e) * ROW + (ci0 + 4 * m) * 2);
-            v4u bv[4];
-#pragma unroll
-            for (int qs = 0; qs < 4; ++qs)
-#pragma unroll
-                for (int wd = 0; wd < 4; ++wd)
-                    bv[qs][wd] = __builtin_amdgcn_perm(xw[2 * wd + 1][qs >> 1], xw[2 * wd][qs >> 1],
-                                                       (qs & 1) ? 0x07060302u : 0x05040100u);
-#pragma unroll
-            for (int qo = 0; qo < 2; ++qo) {
-                v2u dyw[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    dyw[e] = *reinterpret_cast<const v2u *>(buf + DY_OFF + (8 * g + e) * ROW + (co0 + 64 * qo + 4 * m) * 2);
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    v4u av;
-#pragma unroll
-                    for (int wd = 0; wd < 4; ++wd)
-                        av[wd] = __builtin_amdgcn_perm(dyw[2 * wd + 1][qd >> 1], dyw[2 * wd][qd >> 1],
-                                                       (qd & 1) ? 0x07060302u : 0x05040100u);
-#pragma unroll
-                    for (int qs = 0; qs < 4; ++qs)
-                        acc[qo][qd][qs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv[qs]), acc[qo][qd][qs], 0, 0, 0);
+                for (int j = 0; j < 2; ++j) {
+                    const int r = 4 * wave + 2 * j + half;
+                    if (r >= n1) *reinterpret_cast<v4u *>(dst + (r >> 3) * GP + (r & 7) * ROW) = v4u{0u, 0u, 0u, 0u};
                 }
             }
-            if (b0.last) {
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // batch s + 1 is complete in LDS: ask for its first operands, multiply the second half of batch s meanwhile
+        const unsigned char *nbuf = stage + ((cur + 1) & 3) * LDS_BATCH_BYTES;
+        v2u xw[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            xw[e] = *reinterpret_cast<const v2u *>(nbuf + X_OFF + g * GP + e * ROW + (ci0 + 4 * m) * 2);
+        v2u dyn[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            dyn[e] = *reinterpret_cast<const v2u *>(nbuf + DY_OFF + g * GP + e * ROW + (co0 + 4 * m) * 2);
+        if constexpr (COMPUTE) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) multiply(1, qd, dyw1);
+            if (w0 & 256u) {
                 // flush: lane (m, g), register j of acc[qo][qd][qs] is dW[co0 + 64 qo + 4 (4g + j) + qd][ci0 + 4m + qs]
-                float *dstp = part + (size_t)(first ? chunk_id : n_chunks + b0.k) * C * C;
+                float *dstp = part + (size_t)(first ? chunk_id : n_chunks + (w0 >> 16)) * C * C;
 #pragma unroll
                 for (int qo = 0; qo < 2; ++qo)
 #pragma unroll
@@ -526,22 +594,30 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
                 first = false;
             }
         }
-        // rows of batch s + 1 (asked for one step ago) into the other buffer: its readers passed the last barrier
-        {
-            unsigned char *dst = stage + (PAR ^ 1) * LDS_BATCH_BYTES + lds_mine;
-            const bool keep = b1.n > r;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<v4u *>(dst + j * 128) = keep ? rows[PAR ^ 1][j] : v4u{0u, 0u, 0u, 0u};
+        for (int qs = 0; qs < 4; ++qs)
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd)
+                bv[qs][wd] = __builtin_amdgcn_perm(xw[2 * wd + 1][qs >> 1], xw[2 * wd][qs >> 1],
+                                                   (qs & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dyw0[e] = dyn[e];
+        // the indices of batch s + 4 (asked for two steps ago) into registers for the next step's row requests
+        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        {
+            const unsigned char *words = ring + ((cur + 4) & 3) * 256;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                ix[j] = *reinterpret_cast<const int32_t *>(words + 4 * (2 * j + half));
+                io[j] = *reinterpret_cast<const int32_t *>(words + 4 * (4 + 2 * j + half));
+            }
         }
-        __syncthreads();
-        b0 = b1; b1 = b2; b2 = b3; b3 = b4; b4 = next_batch();
+        w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = next_batch();
+        cur = (cur + 1) & 3;
     };
-    while (b0.n | b1.n | b2.n | b3.n | b4.n) {
-        step(std::integral_constant<int, 0>{});
-        if (!(b0.n | b1.n | b2.n | b3.n | b4.n)) break;
-        step(std::integral_constant<int, 1>{});
-    }
+    for (int f = 0; f < 5; ++f) step(std::false_type{});
+    while (w0) step(std::true_type{});
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // nothing of this wave is still on its way into LDS
 }
 
 // dw[k][e] = (partial of the run's head, if it starts inside a chunk) + partials of the chunks whose first
@@ -628,8 +704,8 @@ int launch_weight(const MvmrArgs &a, float *dw, const int32_t *tri_o, const int6
     if (n_chunks > 0) {
         // (16-byte row reads: the entry point has checked that x and dy are 16-byte aligned, and rows are 512 bytes)
         if constexpr (BF16 && C_IN == 256 && C_OUT == 256) {
-            if (int rc = raise_lds_limit(reinterpret_cast<const void *>(&weight_lds_kernel), 2 * LDS_BATCH_BYTES)) return rc;
-            weight_lds_kernel<<<(unsigned)n_chunks, LDS_WAVES * 64, 2 * LDS_BATCH_BYTES, stream>>>(
+            if (int rc = raise_lds_limit(reinterpret_cast<const void *>(&weight_lds_kernel), LDS_WEIGHT_BYTES)) return rc;
+            weight_lds_kernel<<<(unsigned)n_chunks, LDS_WAVES * 64, LDS_WEIGHT_BYTES, stream>>>(
                 static_cast<const uint16_t *>(a.feat), static_cast<const uint16_t *>(a.dense), part, tri_o, a.gather, seg,
                 a.K, a.n_triplets, chunk, n_chunks);
         } else if constexpr (!BF16 && SUB_IN == C_IN && SUB_OUT == C_OUT)
