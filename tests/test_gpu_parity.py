@@ -47,7 +47,7 @@ def check_triplets(T, o, i, k, seg):
 def run_ops(pcpp, scene, T, x, w, dy, o, i, k, ops):
     tol = TOL[scene.dtype]
     dt = feat_dtype(scene)
-    dx_, dw_, ddy = dev(x, dt), dev(w, dt), dev(dy, dt)
+    dx_, dw_, ddy = dev(x, dt), (dev(w, dt) if w is not None else None), dev(dy, dt)
     if "fwd" in ops:
         out = pcpp.pcpp_mvmr_fwd(dx_, dw_, T).cpu().numpy()
         ref, scale = oracle_fwd(x, w, o, i, k, scene.n_out)
@@ -255,7 +255,7 @@ def test_scene5_full_size_sampled(pcpp):
     assert np.array_equal(np.searchsorted(so, tri_o[sel]), o)
     assert np.array_equal(tri_i[sel], i) and np.array_equal(tri_k[sel], k)
     dt = feat_dtype(s)
-    dx_, dw_, ddy = dev(x, dt), dev(w, dt), dev(dy, dt)
+    dx_, dw_, ddy = dev(x, dt), (dev(w, dt) if w is not None else None), dev(dy, dt)
     out = pcpp.pcpp_mvmr_fwd(dx_, dw_, T)
     ui, inv = np.unique(i, return_inverse=True)
     ref, scale = oracle_fwd(x[ui], w, o, inv.astype(np.int32), k, len(so))
@@ -383,6 +383,28 @@ def test_wide_layer_long_lists(pcpp):
     T = build_gpu(pcpp, p, p, r, t, same=True)
     check_triplets(T, o, i, k, seg)
     run_ops(pcpp, s, T, x, w, dy, o, i, k, ("fwd", "bwd_input", "bwd_weight"))
+
+
+@pytest.mark.parametrize("c", [64, 256])
+def test_weight_gradient_short_lists(pcpp, c):
+    """Weight gradient of the bf16 kernels on lists shorter than their pipelines: 1 to 196 triplets in one cell
+    (coincident points), and a sparse cloud in which every cell of a 5^3 kernel holds a handful of triplets."""
+    rng = np.random.default_rng(77 + c)
+    cases = []
+    for n in (1, 2, 5, 6, 8, 11, 14):
+        q = np.tile(np.array([[0.25, 0.5, 0.75]], np.float32), (n, 1))
+        cases.append((q, 0.1, 3))
+    cases.append((rng.uniform(0, 1, (60, 3)).astype(np.float32), 0.3, 5))
+    cases.append((rng.uniform(0, 1, (300, 3)).astype(np.float32), 0.12, 5))
+    for q, r, t in cases:
+        n = len(q)
+        o, i, k, seg = oracle.build_triplets(q, q, np.float32(r), t)
+        T = build_gpu(pcpp, q, q, r, t, same=True)
+        check_triplets(T, o, i, k, seg)
+        x = scenes.round_to_bf16(rng.standard_normal((n, c)).astype(np.float32))
+        dy = scenes.round_to_bf16(rng.standard_normal((n, c)).astype(np.float32))
+        s = scenes.Scene(0, f"short{n}", q, q, float(np.float32(r)), t, c, c, "bf16")
+        run_ops(pcpp, s, T, x, None, dy, o, i, k, ("bwd_weight",))
 
 
 RANDOM_SHAPES = [(32, 32, "f32"), (64, 64, "f32"), (16, 16, "f32"), (64, 64, "bf16"), (64, 128, "bf16"),
