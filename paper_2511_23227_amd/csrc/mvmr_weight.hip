@@ -402,7 +402,9 @@ constexpr int LDS_INDEX_BYTES = LDS_WAVES * LDS_NBUF * 256;   // per wave and ba
                                                               // row 4 w + r in tri_i (a = 0) or tri_o (a = 1)
 constexpr int LDS_WEIGHT_BYTES = LDS_NBUF * LDS_BATCH_BYTES + LDS_INDEX_BYTES;
 
-// 16 bytes per lane from `src` (per lane) to LDS byte address `lds` + 16 lane (`lds` wave-uniform)
+// 16 bytes per lane from `src` (per lane) to LDS byte address `lds` + 16 lane (`lds` wave-uniform).  The address
+// travels in M0, which the statement overwrites without saying so (the compiler reserves the register and refuses it
+// as a clobber); nothing else in a compute kernel for this target lives in M0 (LDS instructions need none here).
 __device__ inline void load_to_lds_b128(const void *src, uint32_t lds)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds) : "memory");
