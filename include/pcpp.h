@@ -111,7 +111,9 @@ PCPP_API int pcpp_version(void);
  *                        aligned; contents are undefined afterwards.  With at least
  *                        pcpp_build_triplets_workspace_bytes_for(..., capacity) bytes the neighbours
  *                        found while counting are kept and the second pass does not search again
- *                        (same results, about a third less time).
+ *                        (same results, about a third less time); a plan in spatial order, which groups
+ *                        the same neighbourhoods a second time, then regroups those lists instead of
+ *                        searching twice.
  * in_xyz [n_in,3] and out_xyz [n_out,3] may alias (outputs at the inputs).
  * Errors: INVALID_ARG (null xyz with n > 0, radius not finite or <= 0, t outside 1..PCPP_MAX_T,
  * some but not all tri_* NULL, unknown flag bits), CAPACITY, WORKSPACE, UNSUPPORTED (|T| >= 2^31), HIP.

@@ -237,6 +237,40 @@ struct Candidates {
         return fetch2<false>(idx, g, q, b, k, k2);
     }
 
+    // Ball mode, the pieces of the test.  d = input - output, in binary64, no contraction.
+    __device__ inline void offset_of(const float4 &p, double &dx, double &dy, double &dz) const
+    {
+        dx = SWAP ? __dsub_rn(cx, (double)p.x) : __dsub_rn((double)p.x, cx);
+        dy = SWAP ? __dsub_rn(cy, (double)p.y) : __dsub_rn((double)p.y, cy);
+        dz = SWAP ? __dsub_rn(cz, (double)p.z) : __dsub_rn((double)p.z, cz);
+    }
+    __device__ static inline bool inside(double dx, double dy, double dz, const QueryParams &q)
+    {
+        return __dadd_rn(__dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy)), __dmul_rn(dz, dz)) <= q.r2;
+    }
+    // kernel cell of the offset, and with MIRROR of the exactly negated offset (what the swapped subtraction gives)
+    template <bool MIRROR>
+    __device__ static inline void cells_of(double dx, double dy, double dz, const QueryParams &q, int &k, int &k2)
+    {
+        const int tm1 = q.t - 1;
+        const double ux = floor(__dmul_rn(__dadd_rn(dx, q.R), q.inv_cell));
+        const double uy = floor(__dmul_rn(__dadd_rn(dy, q.R), q.inv_cell));
+        const double uz = floor(__dmul_rn(__dadd_rn(dz, q.R), q.inv_cell));
+        int kx = ux < 0.0 ? 0 : (int)fmin(ux, (double)tm1);
+        int ky = uy < 0.0 ? 0 : (int)fmin(uy, (double)tm1);
+        int kz = uz < 0.0 ? 0 : (int)fmin(uz, (double)tm1);
+        k = (kx * q.t + ky) * q.t + kz;
+        if constexpr (MIRROR) {
+            const double vx = floor(__dmul_rn(__dadd_rn(-dx, q.R), q.inv_cell));
+            const double vy = floor(__dmul_rn(__dadd_rn(-dy, q.R), q.inv_cell));
+            const double vz = floor(__dmul_rn(__dadd_rn(-dz, q.R), q.inv_cell));
+            const int mx = vx < 0.0 ? 0 : (int)fmin(vx, (double)tm1);
+            const int my = vy < 0.0 ? 0 : (int)fmin(vy, (double)tm1);
+            const int mz = vz < 0.0 ? 0 : (int)fmin(vz, (double)tm1);
+            k2 = (mx * q.t + my) * q.t + mz;
+        }
+    }
+
     template <bool MIRROR>
     __device__ inline bool fetch2(uint32_t idx, const GridView &g, const QueryParams &q, int &b, int &k, int &k2) const
     {
@@ -270,30 +304,10 @@ struct Candidates {
                 }
                 return hit;
             }
-            // d = input - output, in binary64, no contraction
-            const double dx = SWAP ? __dsub_rn(cx, (double)p.x) : __dsub_rn((double)p.x, cx);
-            const double dy = SWAP ? __dsub_rn(cy, (double)p.y) : __dsub_rn((double)p.y, cy);
-            const double dz = SWAP ? __dsub_rn(cz, (double)p.z) : __dsub_rn((double)p.z, cz);
-            const double d2 = __dadd_rn(__dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy)), __dmul_rn(dz, dz));
-            hit = d2 <= q.r2 && (!EXT || (b >= d_lo && b < d_hi));
-            const int tm1 = q.t - 1;
-            const double ux = floor(__dmul_rn(__dadd_rn(dx, q.R), q.inv_cell));
-            const double uy = floor(__dmul_rn(__dadd_rn(dy, q.R), q.inv_cell));
-            const double uz = floor(__dmul_rn(__dadd_rn(dz, q.R), q.inv_cell));
-            int kx = ux < 0.0 ? 0 : (int)fmin(ux, (double)tm1);
-            int ky = uy < 0.0 ? 0 : (int)fmin(uy, (double)tm1);
-            int kz = uz < 0.0 ? 0 : (int)fmin(uz, (double)tm1);
-            k = (kx * q.t + ky) * q.t + kz;
-            if constexpr (MIRROR) {
-                // the swapped subtraction gives exactly the negated offset
-                const double vx = floor(__dmul_rn(__dadd_rn(-dx, q.R), q.inv_cell));
-                const double vy = floor(__dmul_rn(__dadd_rn(-dy, q.R), q.inv_cell));
-                const double vz = floor(__dmul_rn(__dadd_rn(-dz, q.R), q.inv_cell));
-                const int mx = vx < 0.0 ? 0 : (int)fmin(vx, (double)tm1);
-                const int my = vy < 0.0 ? 0 : (int)fmin(vy, (double)tm1);
-                const int mz = vz < 0.0 ? 0 : (int)fmin(vz, (double)tm1);
-                k2 = (mx * q.t + my) * q.t + mz;
-            }
+            double dx, dy, dz;
+            offset_of(p, dx, dy, dz);
+            hit = inside(dx, dy, dz, q) && (!EXT || (b >= d_lo && b < d_hi));
+            cells_of<MIRROR>(dx, dy, dz, q, k, k2);
         }
         return hit;
     }
@@ -315,6 +329,13 @@ constexpr uint32_t HIT_INDEX_MASK = (1u << HIT_INDEX_BITS) - 1u;
 // of the opposite offset.
 struct CountOut {
     uint32_t *tile_cnt, *tile_k_cnt, *hits;
+    uint32_t *n_hits;        // (may be NULL) [n_centres]: every centre's number of neighbours, with `hits`
+};
+// Lists that an earlier count pass over the same centres kept (indexed by centre, not by slot; same stride): a centre
+// whose list is complete is counted from it without a search.  cand_xyz: the candidates' coordinates by index.
+struct Reuse {
+    const uint32_t *hits, *n_hits;
+    const float *cand_xyz;
 };
 
 template <bool SWAP, bool BOTH, bool EXT>
@@ -322,7 +343,7 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
                                                               const int32_t *__restrict__ perm,
                                                               GridView g, QueryParams q, int K, int64_t n_tiles,
                                                               CountOut side, CountOut mirror, uint32_t hit_stride,
-                                                              const uint32_t *__restrict__ err)
+                                                              const uint32_t *__restrict__ err, Reuse reuse)
 {
     extern __shared__ uint32_t tbl[];          // [K][TILE], with BOTH followed by the mirror side's [K][TILE]
     __shared__ uint32_t stage[(BOTH ? 2 : 1) * SEARCH_WAVES * KEEP_MAX];   // hit lists on their way to memory
@@ -334,15 +355,32 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
     for (int idx = threadIdx.x; idx < (BOTH ? 2 : 1) * K * TILE; idx += SEARCH_THREADS) tbl[idx] = 0u;
     __syncthreads();
     const bool keep = side.hits != nullptr;
-    for (int al = wave; al < TILE; al += SEARCH_WAVES) {
+    // With lists to reuse, a centre costs two memory round trips (its list, the coordinates of the listed points) once
+    // its own index, list length and coordinates are known: those of the wave's four centres are fetched together up
+    // front (lane j: index and length of the j-th, lane 3 j + axis: a coordinate).
+    constexpr int PER_WAVE = TILE / SEARCH_WAVES;
+    int pre_ac = 0;
+    uint32_t pre_n = ~0u;
+    float pre_xyz = 0.f;
+    if (!EXT && reuse.hits) {
+        const int64_t a_j = tile * TILE + wave + (int64_t)(lane < PER_WAVE ? lane : 0) * SEARCH_WAVES;
+        if (lane < PER_WAVE && a_j < n_centres) pre_ac = perm ? perm[a_j] : (int)a_j;
+        if (lane < PER_WAVE && a_j < n_centres) pre_n = reuse.n_hits[pre_ac];
+        const int of = lane / 3 < PER_WAVE ? lane / 3 : 0;
+        const int ac_of = __shfl(pre_ac, of, 64);
+        const int64_t a_of = tile * TILE + wave + (int64_t)of * SEARCH_WAVES;
+        if (lane < 3 * PER_WAVE && a_of < n_centres) pre_xyz = centres[3 * (int64_t)ac_of + lane % 3];
+    }
+    int nth = 0;
+    for (int al = wave; al < TILE; al += SEARCH_WAVES, ++nth) {
         const int64_t a = tile * TILE + al;        // slot; the tables and lists are indexed by it
         if (a >= n_centres) break;                 // wave-uniform
+        const bool pre = !EXT && reuse.hits;
+        const int64_t ac = pre ? (int64_t)__shfl(pre_ac, nth, 64) : (perm ? (int64_t)perm[a] : a);     // the centre's index
         Candidates<SWAP, EXT> c;
-        c.open(centres, perm ? (int64_t)perm[a] : a, g, q, lane);
         uint32_t filled = 0;
-        for (uint32_t base = 0; base < c.total; base += 64) {
-            int b, k, k2;
-            const bool hit = c.template fetch2<BOTH>(base + lane, g, q, b, k, k2);
+        // what is done for every neighbour: its cell's counter(s), and its place in the list that is kept
+        auto account = [&](bool hit, int b, int k, int k2) {
             if (hit) {
                 atomicAdd(&tbl[k * TILE + al], 1u);
                 if constexpr (BOTH) atomicAdd(&tbl2[k2 * TILE + al], 1u);
@@ -356,7 +394,45 @@ __global__ __launch_bounds__(SEARCH_THREADS, 8) void query_count(const float *__
                 }
                 filled += (uint32_t)__popcll(m);
             }
+        };
+        bool searched = true;
+        if constexpr (!EXT) {
+            const uint32_t n_known = pre ? (uint32_t)__shfl((int)pre_n, nth, 64) : ~0u;      // wave-uniform
+            if (n_known <= hit_stride) {
+                // the whole neighbourhood is in the earlier pass's list, in the order in which a search finds it
+                searched = false;
+                c.cx = (double)__shfl(pre_xyz, 3 * nth, 64);
+                c.cy = (double)__shfl(pre_xyz, 3 * nth + 1, 64);
+                c.cz = (double)__shfl(pre_xyz, 3 * nth + 2, 64);
+                for (uint32_t e0 = 0; e0 < n_known; e0 += 64) {
+                    const uint32_t e = e0 + (uint32_t)lane;
+                    const bool on = e < n_known;
+                    int b = 0, k = 0, k2 = 0;
+                    if (on) {
+                        const uint32_t key = reuse.hits[(size_t)ac * hit_stride + e];
+                        b = (int)(key & HIT_INDEX_MASK);
+                        k = (int)(key >> HIT_INDEX_BITS);
+                        if constexpr (BOTH) {      // the mirrored cell needs the offset again
+                            const float *pp = reuse.cand_xyz + 3 * (size_t)b;
+                            const float4 p = float4{pp[0], pp[1], pp[2], 0.f};
+                            double dx, dy, dz;
+                            c.offset_of(p, dx, dy, dz);
+                            Candidates<SWAP, EXT>::template cells_of<true>(dx, dy, dz, q, k, k2);
+                        }
+                    }
+                    account(on, b, k, k2);
+                }
+            }
         }
+        if (searched) {
+            c.open(centres, ac, g, q, lane);
+            for (uint32_t base = 0; base < c.total; base += 64) {
+                int b, k, k2;
+                const bool hit = c.template fetch2<BOTH>(base + lane, g, q, b, k, k2);
+                account(hit, b, k, k2);
+            }
+        }
+        if (side.n_hits && lane == 0) side.n_hits[a] = filled;
         if (keep) {                                // one contiguous write per centre
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -843,6 +919,10 @@ struct BuildScratch {
     // that the fill pass need not search again (needs the triplet capacity to size the lists).
     uint32_t fwd_stride = 0, bwd_stride = 0;
     size_t fwd_hits_off = 0, bwd_hits_off = 0, end_with_hits = 0;
+    // Optional, after that: a second set of lists of the outputs and their lengths.  A plan in spatial order counts
+    // the same neighbourhoods twice, once in index order for the public list and once in slot order; with these the
+    // second count reads the first one's lists instead of searching again.
+    size_t pub_hits_off = 0, n_hits_off = 0, end_with_reuse = 0;
 };
 
 // list length per centre: twice the mean neighbour count, within [32, KEEP_MAX]
@@ -885,7 +965,10 @@ BuildScratch build_scratch(int64_t n_in, int64_t n_out, int K, int64_t capacity 
         b.fwd_hits_off = off; off += align_up((size_t)n_out * b.fwd_stride * 4);
         b.bwd_hits_off = off; off += align_up((size_t)n_in * b.bwd_stride * 4);
         b.end_with_hits = off;
+        b.n_hits_off = off;   off += align_up((size_t)n_out * 4);
+        b.pub_hits_off = off; off += align_up((size_t)n_out * b.fwd_stride * 4);
     }
+    b.end_with_reuse = off;
     return b;
 }
 
@@ -975,7 +1058,7 @@ size_t pcpp_build_triplets_workspace_bytes(int64_t n_in, int64_t n_out, int t)
 size_t pcpp_build_triplets_workspace_bytes_for(int64_t n_in, int64_t n_out, int t, int64_t capacity)
 {
     if (n_in < 0 || n_out < 0 || t < 1 || t > PCPP_MAX_T || capacity < 0) return 0;
-    return build_scratch(n_in, n_out, t * t * t, capacity).end_with_hits;
+    return build_scratch(n_in, n_out, t * t * t, capacity).end_with_reuse;
 }
 
 size_t pcpp_plan_bytes(int64_t n_in, int64_t n_out, int t, int64_t n_triplets, int plan_flags)
@@ -1069,6 +1152,7 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
     const bool keep_hits = bs.fwd_stride != 0 && workspace_bytes >= bs.end_with_hits && !wide_keys;
     uint32_t *f_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.fwd_hits_off) : nullptr;
     uint32_t *b_hits = keep_hits ? reinterpret_cast<uint32_t *>(ws + bs.bwd_hits_off) : nullptr;
+    const Reuse no_reuse{nullptr, nullptr, nullptr};
     uint32_t *err = reinterpret_cast<uint32_t *>(ws + bs.err_off);
     auto scan_scratch = [&](int which) -> void * { return ws + bs.scan_off + (size_t)which * bs.scan_stride; };
     const int list_cap = (test_flags & PCPP_BUILD_TEST_SHORT_LISTS) ? 40 : LIST_CAP_MAX;
@@ -1173,21 +1257,27 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
     uint32_t *f_off = fwd_direct ? reinterpret_cast<uint32_t *>(pb + pl.fwd.tile_ptr_off) : f_ptr;
 
     // ---- the public list: centres = outputs in index order, candidates = inputs ------------------------------
+    // With a plan in spatial order the same neighbourhoods are counted again in slot order: given the room, this pass
+    // leaves its lists where that one can read them while it writes its own.
+    const bool reuse_lists = keep_hits && spatial && !ext && !count_only && workspace_bytes >= bs.end_with_reuse;
+    uint32_t *pub_hits = reuse_lists ? reinterpret_cast<uint32_t *>(ws + bs.pub_hits_off) : f_hits;
+    uint32_t *pub_n = reuse_lists ? reinterpret_cast<uint32_t *>(ws + bs.n_hits_off) : nullptr;
+    const Reuse from_public{reuse_lists ? pub_hits : nullptr, pub_n, in_xyz};
     if (nt_o > 0) {
-        const CountOut fwd_out{count_only ? nullptr : f_cnt, f_ptr, f_hits};
+        const CountOut fwd_out{count_only ? nullptr : f_cnt, f_ptr, pub_hits, pub_n};
         if (one_pass && !spatial)
             {
                 if (ext) query_count<false, true, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
-                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err, no_reuse);
                 else query_count<false, true, false><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
-                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err, no_reuse);
             }
         else
             {
                 if (ext) query_count<false, false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
-                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err, no_reuse);
                 else query_count<false, false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
-                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+                out_xyz, n_out, nullptr, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err, no_reuse);
             }
         PCPP_HIP_CHECK(hipGetLastError());
     }
@@ -1239,10 +1329,10 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
         {
                 if (ext) query_fill<false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
             out_xyz, n_out, nullptr, grid_in, q, K, nt_o, f_cnt, f_off, FillOut{tri_o, tri_i, tri_k, nullptr, -1, tri_cap},
-            f_runs, list_cap, f_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
+            f_runs, list_cap, pub_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
                 else query_fill<false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds_fill, stream>>>(
             out_xyz, n_out, nullptr, grid_in, q, K, nt_o, f_cnt, f_off, FillOut{tri_o, tri_i, tri_k, nullptr, -1, tri_cap},
-            f_runs, list_cap, f_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
+            f_runs, list_cap, pub_hits, bs.fwd_stride, seg_offsets, pack_ok, err);
             }
         PCPP_HIP_CHECK(hipGetLastError());
     } else {
@@ -1283,16 +1373,16 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
             if (one_pass)
                 {
                 if (ext) query_count<false, true, true><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
-                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err, from_public);
                 else query_count<false, true, false><<<(unsigned)nt_o, SEARCH_THREADS, 2 * lds, stream>>>(
-                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err);
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, CountOut{b_cnt, b_sum, b_hits}, bs.fwd_stride, err, from_public);
             }
             else
                 {
                 if (ext) query_count<false, false, true><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
-                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err, from_public);
                 else query_count<false, false, false><<<(unsigned)nt_o, SEARCH_THREADS, lds, stream>>>(
-                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err);
+                    out_xyz, n_out, perm_o, grid_in, q, K, nt_o, fwd_out, none, bs.fwd_stride, err, from_public);
             }
             PCPP_HIP_CHECK(hipGetLastError());
         }
@@ -1320,9 +1410,9 @@ int pcpp_build_triplets_batched(const float *in_xyz, int64_t n_in, const float *
         if (nt_i > 0 && !one_pass) {
             {
                 if (ext) query_count<true, false, true><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
-                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
+                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err, no_reuse);
                 else query_count<true, false, false><<<(unsigned)nt_i, SEARCH_THREADS, lds, stream>>>(
-                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err);
+                in_xyz, n_in, perm_i, grid_out, qs, K, nt_i, CountOut{b_cnt, b_sum, b_hits}, none, bs.bwd_stride, err, no_reuse);
             }
             PCPP_HIP_CHECK(hipGetLastError());
         }

@@ -280,18 +280,21 @@ def test_scene5_full_size_sampled(pcpp):
     assert_close(gx[torch.from_numpy(si).cuda()].cpu().numpy(), ref, scale, tol, "scene5 bwd_input (sampled inputs)")
 
 
-def test_build_with_and_without_kept_neighbours(pcpp):
+@pytest.mark.parametrize("spatial,same", [(False, False), (True, False), (True, True)])
+def test_build_with_and_without_kept_neighbours(pcpp, spatial, same):
     """The second pass either ranks the neighbours the count pass kept (large workspace) or searches again
-    (minimal workspace, or lists longer than the kept part): same triplets and same plan either way, and both
-    equal to the oracle's list."""
+    (minimal workspace, or lists longer than the kept part), and the second count of a plan in spatial order either
+    regroups the first one's lists or searches again: same triplets and same plan either way, and both equal to the
+    oracle's list.  Separate centres, and a cloud against itself (one count pass for both sides of the plan)."""
     rng = np.random.default_rng(77)
     # a dense blob among sparse points: some centres have far more neighbours than twice the mean
     pts = np.concatenate([rng.random((3000, 3)) * 2.0, 0.9 + rng.random((500, 3)) * 0.08]).astype(np.float32)
-    out = pts[::3].copy()
+    out = pts if same else pts[::3].copy()
     r, t = 0.12, 3
     o, i, k, seg = oracle.build_triplets(pts, out, r, t)
     L = pcpp.library()
-    din, dout = dev(pts), dev(out)
+    din = dev(pts)
+    dout = din if same else dev(out)
     small = torch.empty(L.pcpp_build_triplets_workspace_bytes(len(pts), len(out), t), dtype=torch.uint8, device="cuda")
     large = torch.empty(L.pcpp_build_triplets_workspace_bytes_for(len(pts), len(out), t, len(o)), dtype=torch.uint8,
                         device="cuda")
@@ -304,7 +307,7 @@ def test_build_with_and_without_kept_neighbours(pcpp):
     for ws in (small, large):
         tri = [torch.empty(len(o), dtype=torch.int32, device="cuda") for _ in range(3)]
         sg = torch.empty(t ** 3 + 1, dtype=torch.int64, device="cuda")
-        flags = B.PLAN_FWD | B.PLAN_BWD_INPUT
+        flags = B.PLAN_FWD | B.PLAN_BWD_INPUT | (B.PLAN_SPATIAL if spatial else 0)
         plan = torch.zeros(L.pcpp_plan_bytes(len(pts), len(out), t, len(o), flags), dtype=torch.uint8, device="cuda")
         n = ctypes.c_int64(0)
         rc = L.pcpp_build_triplets(B._ptr(din), len(pts), B._ptr(dout), len(out), float(r), t, B._ptr(tri[0]),
