@@ -374,21 +374,23 @@ __global__ __launch_bounds__(WAVES * 64) void weight_wide_kernel(const void *__r
 // row of a batch of 32 triplets once (x[i] and dy[o]: 32 x 1 KB) with loads that write straight into LDS
 // (global_load_lds_dwordx4: lane l of the wave writes bytes 16 l .. 16 l + 15 behind the address in M0, so one
 // instruction moves two rows), into a ring of four batch buffers: rows in flight cost no registers, and the
-// batches s + 1 .. s + 3 are on their way while batch s is multiplied.  The triplets' indices travel the same way
+// batches s + 1 .. s + 4 are on their way while batch s is multiplied.  The triplets' indices travel the same way
 // (global_load_lds_dword into a small ring per wave), two batches ahead of their rows.
-//   step s:  request the indices of batch s + 5 | first half of batch s (output channels co0 .. co0 + 63, operands
-//            read during step s - 1) with one request for rows of batch s + 3 behind every four MFMAs, the LDS
-//            reads for the second half under way | wait for the rows of batch s + 1, zero its dy rows past the
-//            batch's end | barrier | read the first operands of batch s + 1, second half of batch s meanwhile |
-//            wait for the indices of batch s + 4, read them into registers
+//   step s:  request the indices of batch s + 6 | first half of batch s (output channels co0 .. co0 + 63, operands
+//            read during step s - 1), the LDS reads for the second half under way | wait for the rows of batch
+//            s + 1, zero its dy rows past the batch's end | barrier | read the first operands of batch s + 1; second
+//            half of batch s meanwhile, with one request for rows of batch s + 4 behind every four MFMAs (into the
+//            buffer that batch s has just left: every wave read its last operands of it before the barrier) |
+//            wait for the indices of batch s + 5, read them into registers
 // The requests are spread between the MFMAs because a request can wait hundreds of cycles for room in the memory
 // pipeline and the wave issues in order: bunched at the head of the step they kept the matrix pipe idle (5.1 ->
 // 4.7 ms on a million-point cloud); with the operands of the next batch read during the second half, LDS reads and
-// MFMAs of the block's lock-stepped waves overlap.
+// MFMAs of the block's lock-stepped waves overlap.  The rows' time in flight matters as well: requested in the second
+// half of a step for the batch four ahead they have two and a half steps (4.55 ms), half a step less costs 6 %.
 // Wave w moves rows 4 w .. 4 w + 3 of x and of dy.  The compiler does not see these loads, so the waits are written
 // by hand; they are exact because every step issues the same five memory instructions per wave, in the same order
 // (one for indices, four for rows; a batch that is short or empty re-reads its last triplet, or triplet 0): behind
-// the rows to wait for, ten younger instructions may still be outstanding, behind the indices nine.  (The partial
+// the rows to wait for, eleven younger instructions may still be outstanding, behind the indices nine.  (The partial
 // sums' stores and the rare reads of a cell's bounds, which the compiler does see, only make these waits stricter.)
 // A batch never crosses the end of a cell's run.  The operands are read from LDS in the layout weight_wide_kernel
 // reads from memory.
@@ -480,7 +482,7 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
     *reinterpret_cast<v4u *>(stage + LDS_NBUF * LDS_BATCH_BYTES + wave * (LDS_NBUF * 256) + lane * 16) = v4u{0u, 0u, 0u, 0u};
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
-    uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0, w4 = 0, w5 = next_batch();      // batches s .. s + 5
+    uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0, w4 = 0, w5 = 0, w6 = next_batch();      // batches s .. s + 6
     int cur = 0;                                  // buffer of batch s
 
     v4f acc[2][4][4];
@@ -513,16 +515,16 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
                 __builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv[qs]), acc[qo][qd][qs], 0, 0, 0);
     };
 
-    // one step; COMPUTE = false for the five steps that fill the pipeline (no batch s yet).  Once a batch has reached
+    // one step; COMPUTE = false for the six steps that fill the pipeline (no batch s yet).  Once a batch has reached
     // the front, every step has one until the chunk is used up, and nothing is left behind the last one.
     auto step = [&](auto compute) __attribute__((always_inline)) {
         constexpr bool COMPUTE = decltype(compute)::value;
-        // indices of batch s + 5
+        // indices of batch s + 6
         {
-            const int n5 = (int)(w5 & 255u);
-            int t = (int)q5 + (r_lane < n5 ? r_lane : n5 - 1);
+            const int n6 = (int)(w6 & 255u);
+            int t = (int)q5 + (r_lane < n6 ? r_lane : n6 - 1);
             if (t < 0) t = 0;
-            load_to_lds_b32(tri_lane + t, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring0 + ((cur + 5) & 3) * 256)));
+            load_to_lds_b32(tri_lane + t, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring0 + ((cur + 6) & 3) * 256)));
         }
         // rows of batch s + 3, one request behind every four MFMAs of the first half of batch s (output channels
         // co0 .. co0 + 63; its operands were read one step ago): a request can wait long for room in the memory
@@ -532,27 +534,13 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             dyw1[e] = *reinterpret_cast<const v2u *>(buf + DY_OFF + g * GP + e * ROW + (co0 + 64 + 4 * m) * 2);
-        {
-            const uint32_t dst = lds0 + (uint32_t)((cur + 3) & 3) * LDS_BATCH_BYTES +
-                                 (uint32_t)((wave >> 1) * GP + 4 * (wave & 1) * ROW);
-            auto request = [&](int i) __attribute__((always_inline)) {
-                const int j = i >> 1;
-                if (i & 1)
-                    load_to_lds_b128(dyb + (size_t)io[j] * ROW,
-                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + DY_OFF + 2 * j * ROW)));
-                else
-                    load_to_lds_b128(xb + (size_t)ix[j] * ROW,
-                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + X_OFF + 2 * j * ROW)));
-            };
+        if constexpr (COMPUTE) {
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                if constexpr (COMPUTE) multiply(0, qd, dyw0);
-                request(qd);
-            }
+            for (int qd = 0; qd < 4; ++qd) multiply(0, qd, dyw0);
         }
         // the rows of batch s + 1 have arrived; past its end the dy rows become zeros (the x rows there repeat the
         // batch's last triplet)
-        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(11)" ::: "memory");
         {
             const int n1 = (int)(w1 & 255u);
             if (n1 > 0 && n1 < 32) {
@@ -575,9 +563,26 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             dyn[e] = *reinterpret_cast<const v2u *>(nbuf + DY_OFF + g * GP + e * ROW + (co0 + 4 * m) * 2);
-        if constexpr (COMPUTE) {
+        {
+            // rows of batch s + 4 into the buffer that batch s has just left (every wave has read its last operands
+            // of it before the barrier), one request behind every four MFMAs of the second half
+            const uint32_t dst = lds0 + (uint32_t)cur * LDS_BATCH_BYTES + (uint32_t)((wave >> 1) * GP + 4 * (wave & 1) * ROW);
+            auto request = [&](int i) __attribute__((always_inline)) {
+                const int j = i >> 1;
+                if (i & 1)
+                    load_to_lds_b128(dyb + (size_t)io[j] * ROW,
+                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + DY_OFF + 2 * j * ROW)));
+                else
+                    load_to_lds_b128(xb + (size_t)ix[j] * ROW,
+                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + X_OFF + 2 * j * ROW)));
+            };
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) multiply(1, qd, dyw1);
+            for (int qd = 0; qd < 4; ++qd) {
+                if constexpr (COMPUTE) multiply(1, qd, dyw1);
+                request(qd);
+            }
+        }
+        if constexpr (COMPUTE) {
             if (w0 & 256u) {
                 // flush: lane (m, g), register j of acc[qo][qd][qs] is dW[co0 + 64 qo + 4 (4g + j) + qd][ci0 + 4m + qs]
                 float *dstp = part + (size_t)(first ? chunk_id : n_chunks + (w0 >> 16)) * C * C;
@@ -604,20 +609,21 @@ __global__ __launch_bounds__(LDS_WAVES * 64, 2) void weight_lds_kernel(const uin
                                                    (qs & 1) ? 0x07060302u : 0x05040100u);
 #pragma unroll
         for (int e = 0; e < 8; ++e) dyw0[e] = dyn[e];
-        // the indices of batch s + 4 (asked for two steps ago) into registers for the next step's row requests
+        // the indices of batch s + 5 (asked for at the head of the step before) into registers for the next step's row
+        // requests
         asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
         {
-            const unsigned char *words = ring + ((cur + 4) & 3) * 256;
+            const unsigned char *words = ring + ((cur + 5) & 3) * 256;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 ix[j] = *reinterpret_cast<const int32_t *>(words + 4 * (2 * j + half));
                 io[j] = *reinterpret_cast<const int32_t *>(words + 4 * (4 + 2 * j + half));
             }
         }
-        w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = next_batch();
+        w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = next_batch();
         cur = (cur + 1) & 3;
     };
-    for (int f = 0; f < 5; ++f) step(std::false_type{});
+    for (int f = 0; f < 6; ++f) step(std::false_type{});
     while (w0) step(std::true_type{});
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // nothing of this wave is still on its way into LDS
 }
